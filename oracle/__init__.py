@@ -1,0 +1,193 @@
+"""CPU oracle (test infrastructure): ctypes access to ``legion_oracle.cpp``.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and ``bench.py``'s cpu_baseline
+leg may import this package.  It shares nothing with the HIP library.
+All arrays are numpy arrays in host memory.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass, field
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "legion_oracle.cpp")
+_LIB = os.path.join(_HERE, "liblegion_oracle.so")
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle with g++ (plain -O2, no tuning flags)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-o", _LIB, _SRC])
+    return _LIB
+
+
+class _Graph(C.Structure):
+    _fields_ = [("num_vertices", C.c_int64), ("indptr", C.c_void_p), ("indptr_bytes", C.c_int32),
+                ("indices", C.c_void_p)]
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        L = C.CDLL(_LIB)
+        vp, i32, i64, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64
+        gp = C.POINTER(_Graph)
+        L.orc_philox4x32_10.argtypes = [vp, vp, vp]
+        L.orc_philox4x32_10.restype = None
+        L.orc_draw64.argtypes = [u64, i64, i32, i32]
+        L.orc_draw64.restype = u64
+        L.orc_sample_row.argtypes = [gp, i64, i32, i32, u64, vp]
+        L.orc_sample_row.restype = i32
+        L.orc_sample_khop.argtypes = [gp, vp, i64, vp, i32, u64]
+        L.orc_sample_khop.restype = vp
+        for name in ("orc_batch_frontier", "orc_batch_nbr", "orc_batch_cnt"):
+            getattr(L, name).argtypes = [vp, i32]
+            getattr(L, name).restype = vp
+        L.orc_batch_frontier_size.argtypes = [vp, i32]
+        L.orc_batch_frontier_size.restype = i64
+        L.orc_batch_gather_size.argtypes = [vp]
+        L.orc_batch_gather_size.restype = i64
+        L.orc_batch_gather_ids.argtypes = [vp]
+        L.orc_batch_gather_ids.restype = vp
+        L.orc_batch_free.argtypes = [vp]
+        L.orc_batch_free.restype = None
+        L.orc_build_hotness.argtypes = [gp, vp, i64, i32, vp, i32, u64, i64, vp, vp]
+        L.orc_build_hotness.restype = i64
+        L.orc_rank_by_hotness.argtypes = [vp, i64, vp]
+        L.orc_rank_by_hotness.restype = None
+        L.orc_plan_topo.argtypes = [gp, vp, u64]
+        L.orc_plan_topo.restype = i64
+        L.orc_plan_feat.argtypes = [i64, i64, u64]
+        L.orc_plan_feat.restype = i64
+        L.orc_fill_topo.argtypes = [gp, vp, i64, vp, vp]
+        L.orc_fill_topo.restype = i64
+        L.orc_fill_feat.argtypes = [vp, i64, vp, i64, vp]
+        L.orc_fill_feat.restype = None
+        L.orc_gather.argtypes = [vp, i64, vp, i64, vp]
+        L.orc_gather.restype = None
+        L.orc_count_hits.argtypes = [vp, i64, vp, i64, i64]
+        L.orc_count_hits.restype = i64
+        _lib = L
+    return _lib
+
+
+def _p(a: np.ndarray) -> int:
+    assert a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data
+
+
+def _copy(ptr: int, n: int) -> np.ndarray:
+    if n == 0:
+        return np.empty(0, dtype=np.int32)
+    return np.ctypeslib.as_array(C.cast(ptr, C.POINTER(C.c_int32)), shape=(n,)).copy()
+
+
+def philox4x32_10(ctr, key) -> np.ndarray:
+    c = np.asarray(ctr, dtype=np.uint32).copy()
+    k = np.asarray(key, dtype=np.uint32).copy()
+    out = np.zeros(4, dtype=np.uint32)
+    _load().orc_philox4x32_10(_p(c), _p(k), _p(out))
+    return out
+
+
+def draw64(rng_seed: int, v: int, hop: int, slot: int) -> int:
+    return int(_load().orc_draw64(rng_seed & (2**64 - 1), v, hop, slot))
+
+
+@dataclass
+class Batch:
+    """Result of sampling one mini-batch.  frontier[0] is the seed list."""
+    frontier: list = field(default_factory=list)
+    nbr: list = field(default_factory=list)       # nbr[h]: [len(frontier[h]), fanouts[h]] int32, -1 padded
+    cnt: list = field(default_factory=list)
+    gather_ids: np.ndarray = None
+
+
+class Oracle:
+    """Holds one CSR graph (int32 or int64 offsets, int32 column ids) and an
+    optional feature table ([V, D] array of any 2- or 4-byte dtype)."""
+
+    def __init__(self, indptr: np.ndarray, indices: np.ndarray, features: np.ndarray | None = None):
+        assert indptr.dtype in (np.int32, np.int64) and indices.dtype == np.int32
+        self.indptr = np.ascontiguousarray(indptr)
+        self.indices = np.ascontiguousarray(indices)
+        self.features = None if features is None else np.ascontiguousarray(features)
+        self.V = int(indptr.shape[0] - 1)
+        self._g = _Graph(self.V, _p(self.indptr), self.indptr.dtype.itemsize, _p(self.indices) if indices.size else None)
+        self._L = _load()
+
+    @property
+    def row_bytes(self) -> int:
+        return int(self.features.shape[1] * self.features.dtype.itemsize)
+
+    def sample_row(self, v: int, hop: int, f: int, rng_seed: int):
+        out = np.empty(f, dtype=np.int32)
+        cnt = self._L.orc_sample_row(C.byref(self._g), v, hop, f, rng_seed & (2**64 - 1), _p(out))
+        return out, int(cnt)
+
+    def sample_khop(self, seeds: np.ndarray, fanouts, rng_seed: int) -> Batch:
+        seeds = np.ascontiguousarray(seeds, dtype=np.int32)
+        fo = np.asarray(fanouts, dtype=np.int32)
+        h = self._L.orc_sample_khop(C.byref(self._g), _p(seeds), seeds.size, _p(fo), fo.size, rng_seed & (2**64 - 1))
+        try:
+            b = Batch()
+            for hop in range(fo.size):
+                n = int(self._L.orc_batch_frontier_size(h, hop))
+                b.frontier.append(_copy(self._L.orc_batch_frontier(h, hop), n))
+                b.nbr.append(_copy(self._L.orc_batch_nbr(h, hop), n * int(fo[hop])).reshape(n, int(fo[hop])))
+                b.cnt.append(_copy(self._L.orc_batch_cnt(h, hop), n))
+            b.gather_ids = _copy(self._L.orc_batch_gather_ids(h), int(self._L.orc_batch_gather_size(h)))
+        finally:
+            self._L.orc_batch_free(h)
+        return b
+
+    def build_hotness(self, train_ids: np.ndarray, batch: int, fanouts, base_seed: int, max_batches: int = -1):
+        train_ids = np.ascontiguousarray(train_ids, dtype=np.int32)
+        fo = np.asarray(fanouts, dtype=np.int32)
+        topo = np.empty(self.V, dtype=np.uint32)
+        feat = np.empty(self.V, dtype=np.uint32)
+        nb = self._L.orc_build_hotness(C.byref(self._g), _p(train_ids), train_ids.size, batch, _p(fo), fo.size,
+                                       base_seed & (2**64 - 1), max_batches, _p(topo), _p(feat))
+        return topo, feat, int(nb)
+
+    def rank_by_hotness(self, hot: np.ndarray) -> np.ndarray:
+        hot = np.ascontiguousarray(hot, dtype=np.uint32)
+        order = np.empty(self.V, dtype=np.int32)
+        self._L.orc_rank_by_hotness(_p(hot), self.V, _p(order))
+        return order
+
+    def plan_topo(self, order: np.ndarray, topo_budget: int) -> int:
+        return int(self._L.orc_plan_topo(C.byref(self._g), _p(order), int(topo_budget)))
+
+    def plan_feat(self, feat_budget: int) -> int:
+        return int(self._L.orc_plan_feat(self.V, self.row_bytes, int(feat_budget)))
+
+    def fill_topo(self, order: np.ndarray, n: int):
+        t_indptr = np.empty(n + 1, dtype=np.int64)
+        total = int(self._L.orc_fill_topo(C.byref(self._g), _p(order), n, _p(t_indptr), None))
+        t_indices = np.empty(total, dtype=np.int32)
+        self._L.orc_fill_topo(C.byref(self._g), _p(order), n, _p(t_indptr), _p(t_indices) if total else None)
+        return t_indptr, t_indices
+
+    def fill_feat(self, order: np.ndarray, n: int) -> np.ndarray:
+        cache = np.empty((n, self.features.shape[1]), dtype=self.features.dtype)
+        self._L.orc_fill_feat(_p(self.features), self.row_bytes, _p(order), n, _p(cache) if n else None)
+        return cache
+
+    def gather(self, ids: np.ndarray) -> np.ndarray:
+        ids = np.ascontiguousarray(ids, dtype=np.int32)
+        out = np.empty((ids.size, self.features.shape[1]), dtype=self.features.dtype)
+        self._L.orc_gather(_p(self.features), self.row_bytes, _p(ids), ids.size, _p(out) if ids.size else None)
+        return out
+
+    def count_hits(self, ids: np.ndarray, order: np.ndarray, n_cached: int) -> int:
+        ids = np.ascontiguousarray(ids, dtype=np.int32)
+        return int(self._L.orc_count_hits(_p(ids), ids.size, _p(order), n_cached, self.V))

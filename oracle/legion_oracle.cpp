@@ -1,0 +1,302 @@
+// CPU oracle for the mini-batch data-preparation path of a cache-based GNN
+// training system (pre-sampling hotness, hotness-ranked topology/feature
+// caches, k-hop uniform neighbour sampling, feature extraction).
+//
+// THIS IS TEST INFRASTRUCTURE.  It is a plain, single-threaded, deliberately
+// slow definition of what the path computes.  Only the tests, the smoke check
+// and the bench's cpu_baseline leg may load it; the product library shares no
+// code with it and never calls it.
+//
+// What the paper fixes, and what this file adds where the paper is silent:
+//   * workflow (Sec. 2.2): pick a mini-batch, uniformly sample several hops of
+//     fixed-size neighbour sets, extract the features of seeds and samples.
+//   * hotness (Sec. 4.2.2, step S1): topology hotness of a vertex grows by one
+//     for every edge traversed out of it; feature hotness grows by one for
+//     every vertex present in a mini-batch's sample result.
+//   * ranking (Algorithm 1 with one GPU per clique): vertices ordered by
+//     descending hotness.  Tie-break (paper silent): ascending vertex id.
+//   * cache size rule (Eq. 3 and Eq. 6): a cached topology row costs
+//     4 bytes per neighbour plus 8 bytes; a cached feature row costs
+//     D * element size.  The cached set is the longest prefix of the ranking
+//     whose total cost does not exceed the budget (paper: "until the size
+//     reaches m"; read as <=).
+//   * cache layout (Sec. 4.2.1): topology cache = CSR over the cached rows in
+//     rank order; feature cache = 2-D array, one row per cached vertex in rank
+//     order.
+//   * RNG (paper silent): Philox4x32-10 (Salmon et al., SC'11), one call per
+//     (seed, vertex, hop, slot).
+//   * subset selection (paper says only "uniform, fixed-size"): rows with
+//     degree <= fanout are returned whole; otherwise Floyd's subset algorithm.
+//   * frontier semantics (paper silent): the next frontier is the ascending
+//     sorted set of the current hop's sampled neighbours; the set of vertices
+//     whose features are extracted is the ascending sorted union of the seeds
+//     and all sampled neighbours.
+//
+// Every function has a pin in tests/ (known-answer vectors, brute force,
+// closed forms or library routines); none is "parity unpinned".
+
+#include <algorithm>
+#include <cstdint>
+#include <cstring>
+#include <vector>
+
+namespace {
+
+struct Graph {
+  int64_t num_vertices;
+  const void* indptr;     // num_vertices + 1 offsets
+  int32_t indptr_bytes;   // 4 or 8
+  const int32_t* indices; // column ids
+};
+
+inline int64_t row_begin(const Graph& g, int64_t v) {
+  if (g.indptr_bytes == 8) return static_cast<const int64_t*>(g.indptr)[v];
+  return static_cast<const int32_t*>(g.indptr)[v];
+}
+
+// ---------------------------------------------------------------------------
+// Philox4x32-10.  Counter c[4], key k[2], ten rounds; the key is bumped by the
+// Weyl constants before every round but the first.
+// ---------------------------------------------------------------------------
+void philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  const uint64_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+  const uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+  uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+  uint32_t k0 = key[0], k1 = key[1];
+  for (int round = 0; round < 10; ++round) {
+    if (round > 0) { k0 += W0; k1 += W1; }
+    const uint64_t p0 = M0 * c0;
+    const uint64_t p1 = M1 * c2;
+    const uint32_t hi0 = static_cast<uint32_t>(p0 >> 32), lo0 = static_cast<uint32_t>(p0);
+    const uint32_t hi1 = static_cast<uint32_t>(p1 >> 32), lo1 = static_cast<uint32_t>(p1);
+    const uint32_t n0 = hi1 ^ c1 ^ k0;
+    const uint32_t n1 = lo1;
+    const uint32_t n2 = hi0 ^ c3 ^ k1;
+    const uint32_t n3 = lo0;
+    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// One 64-bit draw for (rng_seed, vertex, hop, slot): counter = (vertex low
+// word, vertex high word, hop, slot), key = (seed low word, seed high word);
+// the draw is output word 0 (low half) and word 1 (high half).
+uint64_t draw64(uint64_t rng_seed, int64_t v, int32_t hop, int32_t slot) {
+  const uint32_t ctr[4] = {static_cast<uint32_t>(static_cast<uint64_t>(v)),
+                           static_cast<uint32_t>(static_cast<uint64_t>(v) >> 32),
+                           static_cast<uint32_t>(hop), static_cast<uint32_t>(slot)};
+  const uint32_t key[2] = {static_cast<uint32_t>(rng_seed), static_cast<uint32_t>(rng_seed >> 32)};
+  uint32_t out[4];
+  philox4x32_10(ctr, key, out);
+  return static_cast<uint64_t>(out[0]) | (static_cast<uint64_t>(out[1]) << 32);
+}
+
+// Map a 64-bit draw onto {0, ..., n-1}: floor(r * n / 2^64).
+inline uint64_t scale_draw(uint64_t r, uint64_t n) {
+  return static_cast<uint64_t>((static_cast<unsigned __int128>(r) * n) >> 64);
+}
+
+// ---------------------------------------------------------------------------
+// Uniform fixed-size neighbour sample of one vertex (Sec. 2.2, step 2).
+// Returns the number of valid entries; out[] has f entries, -1 padded.
+// ---------------------------------------------------------------------------
+int32_t sample_row(const Graph& g, int64_t v, int32_t hop, int32_t f, uint64_t rng_seed, int32_t* out) {
+  const int64_t s = row_begin(g, v);
+  const int64_t d = row_begin(g, v + 1) - s;
+  for (int32_t i = 0; i < f; ++i) out[i] = -1;
+  if (d <= f) {
+    for (int64_t i = 0; i < d; ++i) out[i] = g.indices[s + i];
+    return static_cast<int32_t>(d);
+  }
+  // Floyd: for j = d-f .. d-1 pick t uniform in [0, j]; take t unless already
+  // taken, in which case take j.
+  std::vector<int64_t> pos;
+  pos.reserve(f);
+  for (int32_t i = 0; i < f; ++i) {
+    const int64_t j = d - f + i;
+    const int64_t t = static_cast<int64_t>(scale_draw(draw64(rng_seed, v, hop, i), static_cast<uint64_t>(j) + 1));
+    const bool taken = std::find(pos.begin(), pos.end(), t) != pos.end();
+    const int64_t p = taken ? j : t;
+    pos.push_back(p);
+    out[i] = g.indices[s + p];
+  }
+  return f;
+}
+
+struct Batch {
+  int32_t n_hops = 0;
+  std::vector<std::vector<int32_t>> frontier; // frontier[h], h = 0..n_hops-1
+  std::vector<std::vector<int32_t>> nbr;      // nbr[h]: frontier[h].size() * fanouts[h]
+  std::vector<std::vector<int32_t>> cnt;      // cnt[h]: frontier[h].size()
+  std::vector<int32_t> gather_ids;
+};
+
+void sorted_unique(std::vector<int32_t>& a) {
+  std::sort(a.begin(), a.end());
+  a.erase(std::unique(a.begin(), a.end()), a.end());
+}
+
+// k-hop sampling of one mini-batch.
+void sample_khop(const Graph& g, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
+                 uint64_t rng_seed, Batch& b) {
+  b.n_hops = n_hops;
+  b.frontier.assign(n_hops, {});
+  b.nbr.assign(n_hops, {});
+  b.cnt.assign(n_hops, {});
+  std::vector<int32_t> all(seeds, seeds + n_seeds);
+  std::vector<int32_t> cur(seeds, seeds + n_seeds);
+  for (int32_t h = 0; h < n_hops; ++h) {
+    const int32_t f = fanouts[h];
+    b.frontier[h] = cur;
+    b.nbr[h].assign(cur.size() * static_cast<size_t>(f), -1);
+    b.cnt[h].assign(cur.size(), 0);
+    std::vector<int32_t> next;
+    for (size_t i = 0; i < cur.size(); ++i) {
+      int32_t* row = b.nbr[h].data() + i * static_cast<size_t>(f);
+      const int32_t c = sample_row(g, cur[i], h, f, rng_seed, row);
+      b.cnt[h][i] = c;
+      for (int32_t k = 0; k < f; ++k)
+        if (row[k] >= 0) next.push_back(row[k]);
+    }
+    all.insert(all.end(), next.begin(), next.end());
+    sorted_unique(next);
+    cur.swap(next);
+  }
+  sorted_unique(all);
+  b.gather_ids.swap(all);
+}
+
+} // namespace
+
+extern "C" {
+
+struct orc_graph {
+  int64_t num_vertices;
+  const void* indptr;
+  int32_t indptr_bytes;
+  const int32_t* indices;
+};
+
+static Graph to_graph(const orc_graph* g) { return Graph{g->num_vertices, g->indptr, g->indptr_bytes, g->indices}; }
+
+void orc_philox4x32_10(const uint32_t* ctr, const uint32_t* key, uint32_t* out) { philox4x32_10(ctr, key, out); }
+
+uint64_t orc_draw64(uint64_t rng_seed, int64_t v, int32_t hop, int32_t slot) { return draw64(rng_seed, v, hop, slot); }
+
+int32_t orc_sample_row(const orc_graph* g, int64_t v, int32_t hop, int32_t f, uint64_t rng_seed, int32_t* out) {
+  return sample_row(to_graph(g), v, hop, f, rng_seed, out);
+}
+
+// --- k-hop sampling: result handle + accessors -----------------------------
+void* orc_sample_khop(const orc_graph* g, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts,
+                      int32_t n_hops, uint64_t rng_seed) {
+  Batch* b = new Batch();
+  sample_khop(to_graph(g), seeds, n_seeds, fanouts, n_hops, rng_seed, *b);
+  return b;
+}
+int64_t orc_batch_frontier_size(const void* h, int32_t hop) { return (int64_t) static_cast<const Batch*>(h)->frontier[hop].size(); }
+const int32_t* orc_batch_frontier(const void* h, int32_t hop) { return static_cast<const Batch*>(h)->frontier[hop].data(); }
+const int32_t* orc_batch_nbr(const void* h, int32_t hop) { return static_cast<const Batch*>(h)->nbr[hop].data(); }
+const int32_t* orc_batch_cnt(const void* h, int32_t hop) { return static_cast<const Batch*>(h)->cnt[hop].data(); }
+int64_t orc_batch_gather_size(const void* h) { return (int64_t) static_cast<const Batch*>(h)->gather_ids.size(); }
+const int32_t* orc_batch_gather_ids(const void* h) { return static_cast<const Batch*>(h)->gather_ids.data(); }
+void orc_batch_free(void* h) { delete static_cast<Batch*>(h); }
+
+// --- pre-sampling hotness (Sec. 4.2.2, S1) ---------------------------------
+// The tablet is consumed in consecutive slices of `batch` ids (last slice may
+// be short); slice b is sampled with rng seed base_seed + b.  max_batches < 0
+// means the whole tablet once.  Returns the number of batches processed.
+int64_t orc_build_hotness(const orc_graph* g, const int32_t* train_ids, int64_t n_train, int32_t batch,
+                          const int32_t* fanouts, int32_t n_hops, uint64_t base_seed, int64_t max_batches,
+                          uint32_t* topo_hot, uint32_t* feat_hot) {
+  const Graph G = to_graph(g);
+  std::memset(topo_hot, 0, sizeof(uint32_t) * G.num_vertices);
+  std::memset(feat_hot, 0, sizeof(uint32_t) * G.num_vertices);
+  int64_t n_batches = (n_train + batch - 1) / batch;
+  if (max_batches >= 0 && max_batches < n_batches) n_batches = max_batches;
+  for (int64_t b = 0; b < n_batches; ++b) {
+    const int64_t lo = b * batch;
+    const int64_t hi = std::min<int64_t>(n_train, lo + batch);
+    Batch res;
+    sample_khop(G, train_ids + lo, hi - lo, fanouts, n_hops, base_seed + static_cast<uint64_t>(b), res);
+    for (int32_t h = 0; h < n_hops; ++h)
+      for (size_t i = 0; i < res.frontier[h].size(); ++i)
+        topo_hot[res.frontier[h][i]] += static_cast<uint32_t>(res.cnt[h][i]); // one per traversed edge
+    for (int32_t u : res.gather_ids) feat_hot[u] += 1;
+  }
+  return n_batches;
+}
+
+// --- ranking (Algorithm 1, one GPU): descending hotness, ascending id -------
+void orc_rank_by_hotness(const uint32_t* hot, int64_t num_vertices, int32_t* order) {
+  for (int64_t v = 0; v < num_vertices; ++v) order[v] = static_cast<int32_t>(v);
+  std::stable_sort(order, order + num_vertices, [hot](int32_t a, int32_t b) { return hot[a] > hot[b]; });
+}
+
+// --- Eq. 3: longest prefix of the topology ranking within the byte budget ---
+int64_t orc_plan_topo(const orc_graph* g, const int32_t* order, uint64_t topo_budget) {
+  const Graph G = to_graph(g);
+  uint64_t used = 0;
+  int64_t n = 0;
+  for (; n < G.num_vertices; ++n) {
+    const int64_t v = order[n];
+    const uint64_t cost = static_cast<uint64_t>(row_begin(G, v + 1) - row_begin(G, v)) * 4u + 8u;
+    if (used + cost > topo_budget) break;
+    used += cost;
+  }
+  return n;
+}
+
+// --- Eq. 6: number of feature rows within the byte budget -------------------
+int64_t orc_plan_feat(int64_t num_vertices, int64_t row_bytes, uint64_t feat_budget) {
+  uint64_t used = 0;
+  int64_t n = 0;
+  for (; n < num_vertices; ++n) {
+    if (used + static_cast<uint64_t>(row_bytes) > feat_budget) break;
+    used += static_cast<uint64_t>(row_bytes);
+  }
+  return n;
+}
+
+// --- cache fill-up (Sec. 4.2.2, S3) -----------------------------------------
+// Topology cache: CSR over the first n ranked vertices.  t_indptr has n + 1
+// entries; t_indices must hold t_indptr[n] entries (call once with
+// t_indices == nullptr to learn the size).
+int64_t orc_fill_topo(const orc_graph* g, const int32_t* order, int64_t n, int64_t* t_indptr, int32_t* t_indices) {
+  const Graph G = to_graph(g);
+  int64_t at = 0;
+  t_indptr[0] = 0;
+  for (int64_t r = 0; r < n; ++r) {
+    const int64_t v = order[r];
+    const int64_t s = row_begin(G, v), e = row_begin(G, v + 1);
+    if (t_indices)
+      for (int64_t k = s; k < e; ++k) t_indices[at + (k - s)] = G.indices[k];
+    at += e - s;
+    t_indptr[r + 1] = at;
+  }
+  return at;
+}
+
+// Feature cache: row r is the feature row of the r-th ranked vertex.
+void orc_fill_feat(const uint8_t* features, int64_t row_bytes, const int32_t* order, int64_t n, uint8_t* cache) {
+  for (int64_t r = 0; r < n; ++r)
+    std::memcpy(cache + r * row_bytes, features + static_cast<int64_t>(order[r]) * row_bytes, row_bytes);
+}
+
+// --- feature extraction (Sec. 5, feature extractor) -------------------------
+void orc_gather(const uint8_t* features, int64_t row_bytes, const int32_t* ids, int64_t n, uint8_t* out) {
+  for (int64_t i = 0; i < n; ++i)
+    std::memcpy(out + i * row_bytes, features + static_cast<int64_t>(ids[i]) * row_bytes, row_bytes);
+}
+
+// Number of ids whose feature row is in the cache holding the first n_cached
+// ranked vertices.
+int64_t orc_count_hits(const int32_t* ids, int64_t n, const int32_t* order, int64_t n_cached, int64_t num_vertices) {
+  std::vector<uint8_t> cached(num_vertices, 0);
+  for (int64_t r = 0; r < n_cached; ++r) cached[order[r]] = 1;
+  int64_t hits = 0;
+  for (int64_t i = 0; i < n; ++i) hits += cached[ids[i]];
+  return hits;
+}
+
+} // extern "C"
