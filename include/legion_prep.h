@@ -1,0 +1,178 @@
+/*
+ * legion_prep -- per-mini-batch data preparation for cache-based GNN training
+ * on one MI355X: pre-sampling hotness, hotness-ranked topology / feature
+ * caches in HBM, k-hop uniform neighbour sampling and feature extraction.
+ *
+ * C ABI.  Every function returns 0 (LGP_OK) or a negative lgp_status; no C++
+ * exception crosses this boundary.  Unless stated otherwise a call only
+ * enqueues work on `stream` (a hipStream_t passed as void*, NULL = the default
+ * stream) and returns without waiting for it.
+ *
+ * Pointer kinds used below
+ *   [host]    ordinary host memory, read or written before the call returns
+ *   [pinned]  host memory that the GPU can address (lgp_host_alloc,
+ *             hipHostMalloc, or a pinned torch tensor); kernels read it in
+ *             place over PCIe.  A device pointer is accepted in its place.
+ *   [device]  memory of the GPU the context was created on
+ * The caller owns every buffer it passes and keeps it alive until the work
+ * that uses it has finished (graph arrays: until lgp_destroy).  The library
+ * owns the context, the caches, the hotness vectors and its scratch memory.
+ * A context must not be used from two threads or two streams at once.
+ */
+#ifndef LEGION_PREP_H
+#define LEGION_PREP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LGP_OK = 0,
+  LGP_EINVAL = -1,       /* null pointer, negative size, id out of range, bad dtype width        */
+  LGP_ESTATE = -2,       /* call order: e.g. build_cache before any hotness exists                */
+  LGP_ECAPACITY = -3,    /* a caller buffer is smaller than the worst case for this call          */
+  LGP_EUNSUPPORTED = -4, /* fanout > LGP_MAX_FANOUT, hops > LGP_MAX_HOPS, V >= 2^31, row too wide  */
+  LGP_EHIP = -5,         /* a HIP runtime call failed; lgp_last_error has the text                */
+  LGP_ENOMEM = -6,       /* device or pinned allocation failed                                    */
+  LGP_EDEVICE = -7       /* a kernel met an invalid vertex id or overran a buffer (sticky flag)   */
+} lgp_status;
+
+#define LGP_MAX_HOPS 8
+#define LGP_MAX_FANOUT 64
+
+typedef struct lgp_ctx lgp_ctx; /* opaque */
+
+/* Graph and feature table as they sit in CPU memory (Sec. 4.2: the full graph lives in
+ * CPU memory; topology is CSR, Eq. 3; features are a V x D array, Eq. 6). */
+typedef struct {
+  int64_t num_vertices;      /* V, 1 <= V < 2^31                                              */
+  int64_t num_edges;         /* E = indptr[V]                                                 */
+  const void* indptr;        /* [pinned] V + 1 row offsets, int32 or int64                    */
+  int32_t indptr_bytes;      /* 4 or 8                                                        */
+  const int32_t* indices;    /* [pinned] E column ids (out-neighbours), each in [0, V)        */
+  const void* features;      /* [pinned] row-major V x D table; may be NULL (no gather then)   */
+  int32_t feat_dim;          /* D                                                             */
+  int32_t elem_bytes;        /* bytes per element: 4 (fp32) or 2 (fp16); rows are opaque bytes */
+} lgp_graph;
+
+/* What lgp_plan_cache / lgp_get_cache_plan report (Eq. 3 and Eq. 6 evaluated on the ranking). */
+typedef struct {
+  int64_t n_topo;            /* vertices whose adjacency is cached                             */
+  int64_t topo_edges;        /* column ids held by the topology cache                          */
+  uint64_t topo_bytes;       /* sum over cached vertices of deg * 4 + 8  (<= topology budget)  */
+  int64_t n_feat;            /* vertices whose feature row is cached                           */
+  uint64_t feat_bytes;       /* n_feat * D * elem_bytes (<= feature budget)                    */
+} lgp_cache_plan;
+
+/* Destination buffers of one lgp_sample_khop call.  Hop h (0-based) expands frontier h
+ * with fan-out fanouts[h]; frontier 0 is the seed list itself.
+ * Worst-case sizes: need[0] = n_seeds, need[h] = min(V, need[h-1] * fanouts[h-1]). */
+typedef struct {
+  int32_t* frontier[LGP_MAX_HOPS]; /* [device] frontier[h], h >= 1: cap[h] ids, ascending, unique; [0] unused */
+  int32_t* nbr[LGP_MAX_HOPS];      /* [device] nbr[h]: cap[h] * fanouts[h]; row i = samples of frontier[h][i],
+                                      -1 padded; rows past n_frontier[h] are left untouched                     */
+  int32_t* cnt[LGP_MAX_HOPS];      /* [device] cnt[h]: cap[h]; valid entries in row i = min(deg, fanout)        */
+  int64_t cap[LGP_MAX_HOPS];       /* capacities in vertices; cap[h] >= need[h] or LGP_ECAPACITY                */
+  int32_t* n_frontier;             /* [device] int32[n_hops]: actual frontier sizes (n_frontier[0] = n_seeds)   */
+  int32_t* gather_ids;             /* [device] ascending unique union of seeds and all sampled neighbours       */
+  int64_t gather_cap;              /* >= min(V, n_seeds + sum_h need[h] * fanouts[h]) or LGP_ECAPACITY          */
+  int32_t* n_gather;               /* [device] int32[1]: number of ids written to gather_ids                    */
+} lgp_sample_out;
+
+/* Accumulated HIP-event timings of the per-batch kernels (see lgp_set_profiling). */
+typedef struct {
+  int64_t n_sample, n_partition, n_hit, n_miss; /* launches / calls timed          */
+  double ms_sample;     /* whole lgp_sample_khop calls (all hops + dedup)          */
+  double ms_partition;  /* cache lookup + hit/miss partition kernel                */
+  double ms_hit;        /* row gather of cache hits (HBM -> HBM)                   */
+  double ms_miss;       /* row gather of misses (pinned host -> HBM over PCIe)     */
+} lgp_profile;
+
+/* Pinned, GPU-addressable host memory for the graph arrays (plain hipHostMalloc /
+ * hipHostFree; synchronous).  lgp_host_alloc returns LGP_ENOMEM on failure. */
+int lgp_host_alloc(size_t bytes, void** out);
+int lgp_host_free(void* ptr);
+
+/* Create a context for `g` on GPU `device`.  Validates sizes and pointer kinds
+ * (LGP_EINVAL if an array is not GPU-addressable), allocates two empty remap
+ * tables, two hotness vectors and the dedup bitmaps (about 16.3 bytes per vertex)
+ * and starts with empty caches, so sampling and gathering already work, entirely
+ * from CPU memory (the "topology in CPU memory" mode of Sec. 3.2).  Synchronous. */
+int lgp_create(const lgp_graph* g, int device, lgp_ctx** out);
+int lgp_destroy(lgp_ctx* ctx);
+
+/* Pre-sampling (Sec. 4.2.2, step S1).  The tablet train_ids [device, n_train ids,
+ * already in epoch order] is cut into consecutive mini-batches of `batch` seeds (the
+ * last may be short); batch b is sampled with rng seed base_seed + b, reading all
+ * topology from CPU memory.  For every expanded vertex its topology hotness grows by
+ * the number of edges sampled out of it; for every distinct vertex of a batch's
+ * result (seeds included) its feature hotness grows by one.  Both vectors are reset
+ * first.  max_batches < 0 processes the whole tablet once.  fanouts is [host]. */
+int lgp_build_hotness(lgp_ctx* ctx, const int32_t* train_ids, int64_t n_train, int32_t batch,
+                      const int32_t* fanouts, int32_t n_hops, uint64_t base_seed, int64_t max_batches,
+                      void* stream);
+
+/* Copy the hotness vectors (uint32[V] each) to / from [host] memory; either pointer
+ * may be NULL.  Synchronous.  lgp_set_hotness lets a saved ranking be reused. */
+int lgp_get_hotness(lgp_ctx* ctx, uint32_t* topo_hot, uint32_t* feat_hot);
+int lgp_set_hotness(lgp_ctx* ctx, const uint32_t* topo_hot, const uint32_t* feat_hot);
+
+/* Cache candidate selection and fill-up (Sec. 4.2.2 steps S2-S3; Algorithm 1 with one
+ * GPU per clique reduces to ranking vertices by descending hotness, ties by ascending
+ * id).  The topology cache takes the longest prefix of the topology ranking whose
+ * cost sum(deg * 4 + 8) stays within topo_budget (Eq. 3); the feature cache takes
+ * min(V, feat_budget / (D * elem_bytes)) rows of the feature ranking (Eq. 6).  Rows
+ * are copied from CPU memory in rank order; cache slot = rank.  Replaces any earlier
+ * cache.  Needs hotness (LGP_ESTATE otherwise).  Allocates device memory and
+ * synchronises `stream`.  lgp_plan_cache only reports the sizes. */
+int lgp_plan_cache(lgp_ctx* ctx, uint64_t topo_budget, uint64_t feat_budget, lgp_cache_plan* plan, void* stream);
+int lgp_build_cache(lgp_ctx* ctx, uint64_t topo_budget, uint64_t feat_budget, void* stream);
+int lgp_get_cache_plan(lgp_ctx* ctx, lgp_cache_plan* plan);
+
+/* Copy the cache to [host] memory for inspection; any pointer may be NULL.
+ * topo_ids[n_topo], t_indptr[n_topo + 1], t_indices[topo_edges], feat_ids[n_feat],
+ * feat_rows[n_feat * D * elem_bytes].  Synchronous. */
+int lgp_get_cache(lgp_ctx* ctx, int32_t* topo_ids, int64_t* t_indptr, int32_t* t_indices, int32_t* feat_ids,
+                  void* feat_rows);
+
+/* k-hop uniform neighbour sampling of one mini-batch (Sec. 2.2 step 2; the neighbour
+ * sampler of Sec. 5).  seeds is [device], n_seeds distinct ids; fanouts is [host],
+ * 1 <= fanouts[h] <= LGP_MAX_FANOUT, 1 <= n_hops <= LGP_MAX_HOPS.  A vertex of degree
+ * d <= fanout yields all its neighbours in CSR order; otherwise `fanout` distinct
+ * positions are chosen by Floyd's subset algorithm from Philox4x32-10 draws keyed by
+ * (rng_seed, vertex, hop, slot).  Adjacency comes from the topology cache when the
+ * vertex is cached, from CPU memory otherwise; the result does not depend on which.
+ * Frontier h + 1 is the ascending unique set of hop h's samples.  No host
+ * synchronisation: sizes stay on the device (out->n_frontier, out->n_gather). */
+int lgp_sample_khop(lgp_ctx* ctx, const int32_t* seeds, int32_t n_seeds, const int32_t* fanouts, int32_t n_hops,
+                    uint64_t rng_seed, const lgp_sample_out* out, void* stream);
+
+/* Feature extraction (Sec. 2.2 step 3; the feature extractor of Sec. 5):
+ * out[i, :] = features[ids[i], :] for i < n, byte for byte.  ids is [device] (any
+ * order, duplicates allowed); n = *n_dev if n_dev [device int32] is given, else n_max;
+ * out is [device] with room for n_max rows.  Ids are split into cache hits (rows read
+ * from the HBM feature cache) and misses (rows read in place from CPU memory over
+ * PCIe); stats [device int32[2], may be NULL] receives {n_hit, n_miss}.  Scratch for
+ * the two lists grows on demand (a growth step allocates and synchronises). */
+int lgp_gather_features(lgp_ctx* ctx, const int32_t* ids, int64_t n_max, const int32_t* n_dev, void* out,
+                        int32_t* stats, void* stream);
+
+/* Sticky device-side error flag (invalid vertex id met by a kernel, output overrun).
+ * Synchronises `stream`, returns LGP_EDEVICE if set, and clears it. */
+int lgp_check(lgp_ctx* ctx, void* stream);
+
+/* HIP-event timing of the per-batch kernels, recorded on the streams they run on.
+ * lgp_get_profile waits for the recorded events, adds them up and resets. */
+int lgp_set_profiling(lgp_ctx* ctx, int enable);
+int lgp_get_profile(lgp_ctx* ctx, lgp_profile* out);
+
+const char* lgp_strerror(int status);
+const char* lgp_last_error(const lgp_ctx* ctx); /* text of the last failure on this context */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LEGION_PREP_H */

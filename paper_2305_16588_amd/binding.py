@@ -1,0 +1,293 @@
+"""Thin ctypes binding of liblegion_prep (argument marshalling only).
+
+PyTorch supplies device memory and streams; every step of the path runs in the
+library's HIP kernels.  There is no CPU fallback: if the library cannot be
+loaded, or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import weakref
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIBPATH = os.path.join(_HERE, "liblegion_prep.so")
+MAX_HOPS = 8
+MAX_FANOUT = 64
+
+
+class LegionPrepError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"legion_prep status {status}: {text}")
+        self.status = status
+
+
+class _Graph(C.Structure):
+    _fields_ = [("num_vertices", C.c_int64), ("num_edges", C.c_int64), ("indptr", C.c_void_p),
+                ("indptr_bytes", C.c_int32), ("indices", C.c_void_p), ("features", C.c_void_p),
+                ("feat_dim", C.c_int32), ("elem_bytes", C.c_int32)]
+
+
+class CachePlan(C.Structure):
+    _fields_ = [("n_topo", C.c_int64), ("topo_edges", C.c_int64), ("topo_bytes", C.c_uint64),
+                ("n_feat", C.c_int64), ("feat_bytes", C.c_uint64)]
+
+
+class _SampleOut(C.Structure):
+    _fields_ = [("frontier", C.c_void_p * MAX_HOPS), ("nbr", C.c_void_p * MAX_HOPS), ("cnt", C.c_void_p * MAX_HOPS),
+                ("cap", C.c_int64 * MAX_HOPS), ("n_frontier", C.c_void_p), ("gather_ids", C.c_void_p),
+                ("gather_cap", C.c_int64), ("n_gather", C.c_void_p)]
+
+
+class Profile(C.Structure):
+    _fields_ = [("n_sample", C.c_int64), ("n_partition", C.c_int64), ("n_hit", C.c_int64), ("n_miss", C.c_int64),
+                ("ms_sample", C.c_double), ("ms_partition", C.c_double), ("ms_hit", C.c_double),
+                ("ms_miss", C.c_double)]
+
+
+EXPORTS = ["lgp_host_alloc", "lgp_host_free", "lgp_create", "lgp_destroy", "lgp_build_hotness", "lgp_get_hotness",
+           "lgp_set_hotness", "lgp_plan_cache", "lgp_build_cache", "lgp_get_cache_plan", "lgp_get_cache",
+           "lgp_sample_khop", "lgp_gather_features", "lgp_check", "lgp_set_profiling", "lgp_get_profile",
+           "lgp_strerror", "lgp_last_error"]
+
+_lib = None
+
+
+def load_library():
+    """Load liblegion_prep.so, building it first only if no built library exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIBPATH):
+        from . import build as _build
+        _build.build()
+    L = C.CDLL(_LIBPATH)
+    vp, i32, i64, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64
+    L.lgp_host_alloc.argtypes = [C.c_size_t, C.POINTER(vp)]
+    L.lgp_host_free.argtypes = [vp]
+    L.lgp_create.argtypes = [C.POINTER(_Graph), C.c_int, C.POINTER(vp)]
+    L.lgp_destroy.argtypes = [vp]
+    L.lgp_build_hotness.argtypes = [vp, vp, i64, i32, vp, i32, u64, i64, vp]
+    L.lgp_get_hotness.argtypes = [vp, vp, vp]
+    L.lgp_set_hotness.argtypes = [vp, vp, vp]
+    L.lgp_plan_cache.argtypes = [vp, u64, u64, C.POINTER(CachePlan), vp]
+    L.lgp_build_cache.argtypes = [vp, u64, u64, vp]
+    L.lgp_get_cache_plan.argtypes = [vp, C.POINTER(CachePlan)]
+    L.lgp_get_cache.argtypes = [vp, vp, vp, vp, vp, vp]
+    L.lgp_sample_khop.argtypes = [vp, vp, i32, vp, i32, u64, C.POINTER(_SampleOut), vp]
+    L.lgp_gather_features.argtypes = [vp, vp, i64, vp, vp, vp, vp]
+    L.lgp_check.argtypes = [vp, vp]
+    L.lgp_set_profiling.argtypes = [vp, C.c_int]
+    L.lgp_get_profile.argtypes = [vp, C.POINTER(Profile)]
+    L.lgp_strerror.argtypes = [C.c_int]
+    L.lgp_strerror.restype = C.c_char_p
+    L.lgp_last_error.argtypes = [vp]
+    L.lgp_last_error.restype = C.c_char_p
+    for name in EXPORTS[:-2]:
+        getattr(L, name).restype = C.c_int
+    _lib = L
+    return L
+
+
+def pinned_empty(shape, dtype) -> np.ndarray:
+    """numpy array in pinned, GPU-addressable host memory (lgp_host_alloc)."""
+    L = load_library()
+    dtype = np.dtype(dtype)
+    shape = (shape,) if np.isscalar(shape) else tuple(int(s) for s in shape)
+    nbytes = int(np.prod(shape, dtype=np.int64)) * dtype.itemsize
+    ptr = C.c_void_p()
+    st = L.lgp_host_alloc(max(nbytes, 1), C.byref(ptr))
+    if st != 0:
+        raise LegionPrepError(st, f"pinned allocation of {nbytes} bytes failed")
+    buf = (C.c_char * max(nbytes, 1)).from_address(ptr.value)
+    arr = np.frombuffer(buf, dtype=dtype, count=int(np.prod(shape, dtype=np.int64))).reshape(shape)
+    weakref.finalize(buf, L.lgp_host_free, ptr.value)
+    return arr
+
+
+def pinned_copy(a: np.ndarray) -> np.ndarray:
+    out = pinned_empty(a.shape, a.dtype)
+    out[...] = a
+    return out
+
+
+def _stream_ptr(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def worst_case_sizes(num_vertices: int, n_seeds: int, fanouts):
+    """need[h] and the gather-set bound, as the header defines them."""
+    need = [int(n_seeds)]
+    total = int(n_seeds)
+    for h, f in enumerate(fanouts):
+        samples = need[h] * int(f)
+        total += samples
+        if h + 1 < len(fanouts):
+            need.append(min(num_vertices, samples))
+    return need, min(num_vertices, total)
+
+
+class SampleBuffers:
+    """Device buffers for one lgp_sample_khop call, sized for the worst case."""
+
+    def __init__(self, num_vertices: int, max_seeds: int, fanouts, device="cuda:0"):
+        self.fanouts = [int(f) for f in fanouts]
+        self.need, self.gather_cap = worst_case_sizes(num_vertices, max_seeds, self.fanouts)
+        dev = torch.device(device)
+        L = len(self.fanouts)
+        self.frontier = [None] + [torch.empty(self.need[h], dtype=torch.int32, device=dev) for h in range(1, L)]
+        self.nbr = [torch.empty((self.need[h], self.fanouts[h]), dtype=torch.int32, device=dev) for h in range(L)]
+        self.cnt = [torch.empty(self.need[h], dtype=torch.int32, device=dev) for h in range(L)]
+        self.n_frontier = torch.zeros(L, dtype=torch.int32, device=dev)
+        self.gather_ids = torch.empty(self.gather_cap, dtype=torch.int32, device=dev)
+        self.n_gather = torch.zeros(1, dtype=torch.int32, device=dev)
+        o = _SampleOut()
+        for h in range(L):
+            o.frontier[h] = self.frontier[h].data_ptr() if h else None
+            o.nbr[h] = self.nbr[h].data_ptr()
+            o.cnt[h] = self.cnt[h].data_ptr()
+            o.cap[h] = self.need[h]
+        o.n_frontier = self.n_frontier.data_ptr()
+        o.gather_ids = self.gather_ids.data_ptr()
+        o.gather_cap = self.gather_cap
+        o.n_gather = self.n_gather.data_ptr()
+        self.c_struct = o
+
+    def to_host(self, seeds: torch.Tensor):
+        """Synchronise and return (frontier, nbr, cnt, gather_ids) trimmed to their actual sizes (numpy)."""
+        n = self.n_frontier.cpu().tolist()
+        fr = [seeds.cpu().numpy()] + [self.frontier[h][:n[h]].cpu().numpy() for h in range(1, len(n))]
+        nbr = [self.nbr[h][:n[h]].cpu().numpy() for h in range(len(n))]
+        cnt = [self.cnt[h][:n[h]].cpu().numpy() for h in range(len(n))]
+        ng = int(self.n_gather.item())
+        return fr, nbr, cnt, self.gather_ids[:ng].cpu().numpy()
+
+
+class Context:
+    """One graph + feature table in pinned CPU memory, its caches and scratch on one GPU.
+
+    indptr / indices / features: numpy arrays from pinned_empty / pinned_copy, or pinned
+    torch tensors.  Method names mirror the C entry points.
+    """
+
+    def __init__(self, indptr, indices, features=None, device: int = 0):
+        self._L = load_library()
+        self._keep = (indptr, indices, features)
+        def ptr(a):
+            return a.data_ptr() if isinstance(a, torch.Tensor) else a.ctypes.data
+        def isz(a):
+            return a.element_size() if isinstance(a, torch.Tensor) else a.dtype.itemsize
+        g = _Graph()
+        g.num_vertices = int(indptr.shape[0]) - 1
+        g.num_edges = int(indices.shape[0])
+        g.indptr = ptr(indptr)
+        g.indptr_bytes = isz(indptr)
+        g.indices = ptr(indices) if g.num_edges else None
+        if features is not None:
+            g.features = ptr(features)
+            g.feat_dim = int(features.shape[1])
+            g.elem_bytes = isz(features)
+            self.feat_torch_dtype = {2: torch.float16, 4: torch.float32}.get(g.elem_bytes, torch.uint8)
+        self.num_vertices = g.num_vertices
+        self.feat_dim = int(g.feat_dim)
+        self.elem_bytes = int(g.elem_bytes)
+        self.device = torch.device(f"cuda:{device}")
+        h = C.c_void_p()
+        st = self._L.lgp_create(C.byref(g), device, C.byref(h))
+        if st != 0:
+            raise LegionPrepError(st, self._L.lgp_strerror(st).decode())
+        self._h = h
+        self._fin = weakref.finalize(self, self._L.lgp_destroy, h)
+
+    def close(self):
+        self._fin()
+
+    def _ok(self, st: int):
+        if st != 0:
+            raise LegionPrepError(st, self._L.lgp_strerror(st).decode() + " -- " +
+                                  self._L.lgp_last_error(self._h).decode())
+
+    @staticmethod
+    def _fanouts(fanouts):
+        return np.ascontiguousarray(fanouts, dtype=np.int32)
+
+    def build_hotness(self, train_ids: torch.Tensor, batch: int, fanouts, base_seed: int, max_batches: int = -1,
+                      stream=None):
+        assert train_ids.is_cuda and train_ids.dtype == torch.int32 and train_ids.is_contiguous()
+        fo = self._fanouts(fanouts)
+        self._ok(self._L.lgp_build_hotness(self._h, train_ids.data_ptr(), train_ids.numel(), batch, fo.ctypes.data,
+                                           fo.size, base_seed & (2**64 - 1), max_batches, _stream_ptr(stream)))
+
+    def get_hotness(self):
+        topo = np.empty(self.num_vertices, dtype=np.uint32)
+        feat = np.empty(self.num_vertices, dtype=np.uint32)
+        self._ok(self._L.lgp_get_hotness(self._h, topo.ctypes.data, feat.ctypes.data))
+        return topo, feat
+
+    def set_hotness(self, topo: np.ndarray, feat: np.ndarray):
+        topo = np.ascontiguousarray(topo, dtype=np.uint32)
+        feat = np.ascontiguousarray(feat, dtype=np.uint32)
+        assert topo.size == self.num_vertices and feat.size == self.num_vertices
+        self._ok(self._L.lgp_set_hotness(self._h, topo.ctypes.data, feat.ctypes.data))
+
+    def plan_cache(self, topo_budget: int, feat_budget: int, stream=None) -> CachePlan:
+        p = CachePlan()
+        self._ok(self._L.lgp_plan_cache(self._h, int(topo_budget), int(feat_budget), C.byref(p), _stream_ptr(stream)))
+        return p
+
+    def build_cache(self, topo_budget: int, feat_budget: int, stream=None) -> CachePlan:
+        self._ok(self._L.lgp_build_cache(self._h, int(topo_budget), int(feat_budget), _stream_ptr(stream)))
+        return self.get_cache_plan()
+
+    def get_cache_plan(self) -> CachePlan:
+        p = CachePlan()
+        self._ok(self._L.lgp_get_cache_plan(self._h, C.byref(p)))
+        return p
+
+    def get_cache(self):
+        p = self.get_cache_plan()
+        topo_ids = np.empty(p.n_topo, dtype=np.int32)
+        t_indptr = np.empty(p.n_topo + 1, dtype=np.int64)
+        t_indices = np.empty(p.topo_edges, dtype=np.int32)
+        feat_ids = np.empty(p.n_feat, dtype=np.int32)
+        feat_rows = np.empty((p.n_feat, self.feat_dim * self.elem_bytes), dtype=np.uint8)
+        self._ok(self._L.lgp_get_cache(self._h, topo_ids.ctypes.data, t_indptr.ctypes.data, t_indices.ctypes.data,
+                                       feat_ids.ctypes.data, feat_rows.ctypes.data))
+        return topo_ids, t_indptr, t_indices, feat_ids, feat_rows
+
+    def sample_khop(self, seeds: torch.Tensor, fanouts, rng_seed: int, out: SampleBuffers | None = None,
+                    stream=None) -> SampleBuffers:
+        assert seeds.is_cuda and seeds.dtype == torch.int32 and seeds.is_contiguous()
+        fo = self._fanouts(fanouts)
+        if out is None:
+            out = SampleBuffers(self.num_vertices, seeds.numel(), fo.tolist(), self.device)
+        self._ok(self._L.lgp_sample_khop(self._h, seeds.data_ptr(), seeds.numel(), fo.ctypes.data, fo.size,
+                                         rng_seed & (2**64 - 1), C.byref(out.c_struct), _stream_ptr(stream)))
+        return out
+
+    def gather_features(self, ids: torch.Tensor, n_dev: torch.Tensor | None = None, out: torch.Tensor | None = None,
+                        stats: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+        assert ids.is_cuda and ids.dtype == torch.int32 and ids.is_contiguous()
+        n_max = ids.numel()
+        if out is None:
+            out = torch.empty((n_max, self.feat_dim), dtype=self.feat_torch_dtype, device=self.device)
+        assert out.is_cuda and out.is_contiguous() and out.numel() * out.element_size() >= n_max * self.feat_dim * self.elem_bytes
+        self._ok(self._L.lgp_gather_features(self._h, ids.data_ptr(), n_max,
+                                             None if n_dev is None else n_dev.data_ptr(), out.data_ptr(),
+                                             None if stats is None else stats.data_ptr(), _stream_ptr(stream)))
+        return out
+
+    def check(self, stream=None):
+        self._ok(self._L.lgp_check(self._h, _stream_ptr(stream)))
+
+    def set_profiling(self, enable: bool):
+        self._ok(self._L.lgp_set_profiling(self._h, int(bool(enable))))
+
+    def get_profile(self) -> Profile:
+        p = Profile()
+        self._ok(self._L.lgp_get_profile(self._h, C.byref(p)))
+        return p

@@ -1,0 +1,682 @@
+// C ABI of liblegion_prep: argument checking, context state, launch sequencing.
+// No arithmetic of the method lives here; every step runs in the kernels.
+#include "common.hpp"
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+using namespace lgp;
+
+namespace {
+
+enum ProfKind { PK_SAMPLE = 0, PK_PARTITION = 1, PK_HIT = 2, PK_MISS = 3, PK_COUNT = 4 };
+
+struct EvPair {
+  hipEvent_t a, b;
+  int kind;
+};
+
+}  // namespace
+
+struct lgp_ctx {
+  DeviceInfo di;
+  lgp_graph g{};           // pointers already translated to device-visible addresses
+  int64_t row_bytes = 0;
+  int64_t n_chunks = 0;    // dedup bitmap chunks
+
+  int32_t* t_remap = nullptr;
+  int32_t* f_remap = nullptr;
+  uint32_t* topo_hot = nullptr;
+  uint32_t* feat_hot = nullptr;
+  bool have_hot = false;
+  uint64_t* fbits = nullptr;   // frontier dedup bitmap
+  uint64_t* gbits = nullptr;   // gather-set dedup bitmap
+  int32_t* chunk_counts = nullptr;
+  uint32_t* d_err = nullptr;
+  int32_t* counters = nullptr;  // {n_hit, n_miss}
+
+  // caches
+  int32_t* order_t = nullptr;
+  int32_t* order_f = nullptr;
+  int64_t* t_indptr = nullptr;
+  int32_t* t_indices = nullptr;
+  void* fc = nullptr;
+  CachePlan plan;
+
+  // gather scratch: hit / miss lists
+  int32_t* lists = nullptr;
+  int64_t list_cap = 0;
+
+  // pre-sampling scratch
+  int32_t* hs_frontier[LGP_MAX_HOPS] = {};
+  int64_t hs_cap[LGP_MAX_HOPS] = {};
+  int32_t* hs_n = nullptr;
+
+  hipStream_t miss_stream = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+
+  bool profiling = false;
+  std::vector<EvPair> ev_used;
+  std::vector<EvPair> ev_free;
+
+  std::string last_error;
+};
+
+namespace {
+
+int fail(lgp_ctx* ctx, int status, const std::string& what) {
+  if (ctx) ctx->last_error = what;
+  return status;
+}
+
+int fail_hip(lgp_ctx* ctx, hipError_t e, const char* what) {
+  (void)hipGetLastError();
+  const int st = (e == hipErrorOutOfMemory) ? LGP_ENOMEM : LGP_EHIP;
+  return fail(ctx, st, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+#define LGP_HIP(ctx, call)                                    \
+  do {                                                        \
+    hipError_t e_ = (call);                                   \
+    if (e_ != hipSuccess) return fail_hip((ctx), e_, #call); \
+  } while (0)
+
+// Resolve a caller pointer to an address kernels can use.
+int device_visible(lgp_ctx* ctx, const void* p, const void** out, const char* name) {
+  hipPointerAttribute_t attr;
+  std::memset(&attr, 0, sizeof(attr));
+  hipError_t e = hipPointerGetAttributes(&attr, p);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(ctx, LGP_EINVAL, std::string(name) + " is not pinned host memory nor device memory");
+  }
+  if (attr.type == hipMemoryTypeHost) {
+    void* d = nullptr;
+    e = hipHostGetDevicePointer(&d, const_cast<void*>(p), 0);
+    if (e != hipSuccess || !d) {
+      (void)hipGetLastError();
+      return fail(ctx, LGP_EINVAL, std::string(name) + " is pinned but not mapped into the GPU address space");
+    }
+    *out = d;
+    return LGP_OK;
+  }
+  if (attr.type == hipMemoryTypeDevice || attr.type == hipMemoryTypeManaged) {
+    *out = p;
+    return LGP_OK;
+  }
+  return fail(ctx, LGP_EINVAL, std::string(name) + " is not pinned host memory nor device memory");
+}
+
+template <typename T>
+hipError_t dev_alloc(T** p, size_t count) {
+  return hipMalloc(reinterpret_cast<void**>(p), std::max<size_t>(count, 1) * sizeof(T));
+}
+
+void free_cache(lgp_ctx* c) {
+  if (c->t_indptr) (void)hipFree(c->t_indptr);
+  if (c->t_indices) (void)hipFree(c->t_indices);
+  if (c->fc) (void)hipFree(c->fc);
+  c->t_indptr = nullptr;
+  c->t_indices = nullptr;
+  c->fc = nullptr;
+  c->plan = CachePlan();
+}
+
+TopoView topo_view(const lgp_ctx* c, bool use_cache) {
+  TopoView tv;
+  tv.h_indptr = c->g.indptr;
+  tv.h_indices = c->g.indices;
+  tv.t_remap = (use_cache && c->plan.n_topo > 0) ? c->t_remap : nullptr;
+  tv.t_indptr = c->t_indptr;
+  tv.t_indices = c->t_indices;
+  tv.indptr_bytes = c->g.indptr_bytes;
+  tv.num_vertices = c->g.num_vertices;
+  return tv;
+}
+
+int check_fanouts(lgp_ctx* ctx, const int32_t* fanouts, int32_t n_hops) {
+  if (!fanouts) return fail(ctx, LGP_EINVAL, "fanouts is null");
+  if (n_hops < 1) return fail(ctx, LGP_EINVAL, "n_hops must be >= 1");
+  if (n_hops > LGP_MAX_HOPS) return fail(ctx, LGP_EUNSUPPORTED, "n_hops exceeds LGP_MAX_HOPS");
+  for (int h = 0; h < n_hops; ++h) {
+    if (fanouts[h] < 1) return fail(ctx, LGP_EINVAL, "fanout must be >= 1");
+    if (fanouts[h] > LGP_MAX_FANOUT) return fail(ctx, LGP_EUNSUPPORTED, "fanout exceeds LGP_MAX_FANOUT");
+  }
+  return LGP_OK;
+}
+
+// Worst-case frontier sizes: need[0] = n_seeds, need[h] = min(V, need[h-1] * f[h-1]).
+void worst_case(const lgp_ctx* c, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops, int64_t* need,
+                int64_t* gather_need) {
+  const int64_t V = c->g.num_vertices;
+  int64_t total = n_seeds;
+  need[0] = n_seeds;
+  for (int h = 0; h < n_hops; ++h) {
+    const int64_t samples = need[h] * fanouts[h];
+    total += samples;
+    if (h + 1 < n_hops) need[h + 1] = std::min(V, samples);
+  }
+  *gather_need = std::min(V, total);
+}
+
+EvPair prof_begin(lgp_ctx* c, int kind, hipStream_t s) {
+  EvPair p{nullptr, nullptr, kind};
+  if (!c->profiling) return p;
+  if (!c->ev_free.empty()) {
+    p = c->ev_free.back();
+    c->ev_free.pop_back();
+    p.kind = kind;
+  } else {
+    if (hipEventCreate(&p.a) != hipSuccess || hipEventCreate(&p.b) != hipSuccess) {
+      (void)hipGetLastError();
+      p.a = p.b = nullptr;
+      return p;
+    }
+  }
+  (void)hipEventRecord(p.a, s);
+  return p;
+}
+
+void prof_end(lgp_ctx* c, EvPair& p, hipStream_t s) {
+  if (!p.a) return;
+  (void)hipEventRecord(p.b, s);
+  c->ev_used.push_back(p);
+}
+
+// Sampling of one mini-batch; out == nullptr is the pre-sampling mode (hotness only).
+int sample_core(lgp_ctx* c, const int32_t* seeds, int32_t n_seeds, const int32_t* fanouts, int32_t n_hops,
+                uint64_t rng_seed, const lgp_sample_out* out, hipStream_t s) {
+  const bool hot_mode = (out == nullptr);
+  const int64_t V = c->g.num_vertices;
+  uint32_t* fbits32 = reinterpret_cast<uint32_t*>(c->fbits);
+  uint32_t* gbits32 = reinterpret_cast<uint32_t*>(c->gbits);
+  int32_t* n_frontier = hot_mode ? c->hs_n : out->n_frontier;
+  const TopoView tv = topo_view(c, !hot_mode);
+
+  launch_mark_ids(c->di, seeds, n_seeds, V, gbits32, n_frontier, c->d_err, s);
+  const int32_t* frontier = seeds;
+  int64_t cap = n_seeds;
+  for (int h = 0; h < n_hops; ++h) {
+    const bool last = (h + 1 == n_hops);
+    // the last hop's samples only feed the gather set, so they are marked there directly
+    launch_sample_hop(c->di, tv, frontier, n_frontier + h, cap, fanouts[h], h, rng_seed,
+                      hot_mode ? nullptr : out->nbr[h], hot_mode ? nullptr : out->cnt[h], last ? gbits32 : fbits32,
+                      hot_mode ? c->topo_hot : nullptr, c->d_err, s);
+    if (!last) {
+      int32_t* next = hot_mode ? c->hs_frontier[h + 1] : out->frontier[h + 1];
+      const int64_t next_cap = hot_mode ? c->hs_cap[h + 1] : out->cap[h + 1];
+      launch_compact(c->di, c->fbits, c->gbits, c->n_chunks, c->chunk_counts, next, next_cap, n_frontier + h + 1,
+                     nullptr, c->d_err, s);
+      frontier = next;
+      cap = next_cap;
+    }
+  }
+  if (hot_mode)
+    launch_compact(c->di, c->gbits, nullptr, c->n_chunks, c->chunk_counts, nullptr, 0, nullptr, c->feat_hot, c->d_err,
+                   s);
+  else
+    launch_compact(c->di, c->gbits, nullptr, c->n_chunks, c->chunk_counts, out->gather_ids, out->gather_cap,
+                   out->n_gather, nullptr, c->d_err, s);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail_hip(c, e, "sampling kernel launch");
+  return LGP_OK;
+}
+
+// Ranking + Eq. 3 / Eq. 6 sizes.  Leaves order_t / order_f filled; returns the
+// cost scan (caller frees) when keep_scan is set.
+int plan_core(lgp_ctx* c, uint64_t topo_budget, uint64_t feat_budget, CachePlan* plan, uint64_t** keep_scan,
+              hipStream_t s) {
+  const int64_t V = c->g.num_vertices;
+  if (!c->have_hot) return fail(c, LGP_ESTATE, "no hotness yet: call lgp_build_hotness or lgp_set_hotness first");
+  if (!c->order_t) LGP_HIP(c, dev_alloc(&c->order_t, size_t(V)));
+  if (!c->order_f) LGP_HIP(c, dev_alloc(&c->order_f, size_t(V)));
+  LGP_HIP(c, rank_by_hotness(c->topo_hot, V, c->order_t, s));
+  LGP_HIP(c, rank_by_hotness(c->feat_hot, V, c->order_f, s));
+
+  int32_t* deg = nullptr;
+  uint64_t* scan = nullptr;
+  uint64_t* result = nullptr;
+  int st = LGP_OK;
+  hipError_t e = dev_alloc(&deg, size_t(V));
+  if (e == hipSuccess) e = dev_alloc(&scan, size_t(V));
+  if (e == hipSuccess) e = dev_alloc(&result, 2);
+  uint64_t host_result[2] = {0, 0};
+  if (e == hipSuccess) {
+    launch_degrees(c->di, c->g.indptr, c->g.indptr_bytes, V, deg, s);
+    e = scan_topo_cost(deg, c->order_t, V, scan, s);
+  }
+  if (e == hipSuccess) {
+    launch_prefix_within_budget(scan, V, topo_budget, result, s);
+    e = hipMemcpyAsync(host_result, result, sizeof(host_result), hipMemcpyDeviceToHost, s);
+  }
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e != hipSuccess) st = fail_hip(c, e, "cache planning");
+  if (deg) (void)hipFree(deg);
+  if (result) (void)hipFree(result);
+  if (st == LGP_OK) {
+    plan->n_topo = int64_t(host_result[0]);
+    plan->topo_bytes = host_result[1];
+    plan->topo_edges = int64_t((host_result[1] - 8u * host_result[0]) / 4u);
+    plan->n_feat = (c->row_bytes > 0 && c->g.features) ? std::min<int64_t>(V, int64_t(feat_budget / uint64_t(c->row_bytes))) : 0;
+    plan->feat_bytes = uint64_t(plan->n_feat) * uint64_t(c->row_bytes);
+  }
+  if (keep_scan && st == LGP_OK) *keep_scan = scan;
+  else if (scan) (void)hipFree(scan);
+  return st;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* lgp_strerror(int status) {
+  switch (status) {
+    case LGP_OK: return "ok";
+    case LGP_EINVAL: return "invalid argument";
+    case LGP_ESTATE: return "call made in the wrong state";
+    case LGP_ECAPACITY: return "caller buffer too small for the worst case";
+    case LGP_EUNSUPPORTED: return "unsupported size or width";
+    case LGP_EHIP: return "HIP runtime error";
+    case LGP_ENOMEM: return "out of memory";
+    case LGP_EDEVICE: return "a kernel reported an invalid vertex id or a buffer overrun";
+    default: return "unknown status";
+  }
+}
+
+const char* lgp_last_error(const lgp_ctx* ctx) { return ctx ? ctx->last_error.c_str() : ""; }
+
+int lgp_host_alloc(size_t bytes, void** out) {
+  if (!out) return LGP_EINVAL;
+  *out = nullptr;
+  void* p = nullptr;
+  hipError_t e = hipHostMalloc(&p, bytes ? bytes : 1, hipHostMallocDefault);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return LGP_ENOMEM;
+  }
+  *out = p;
+  return LGP_OK;
+}
+
+int lgp_host_free(void* ptr) {
+  if (!ptr) return LGP_OK;
+  if (hipHostFree(ptr) != hipSuccess) {
+    (void)hipGetLastError();
+    return LGP_EHIP;
+  }
+  return LGP_OK;
+}
+
+int lgp_create(const lgp_graph* g, int device, lgp_ctx** out) {
+  if (!g || !out) return LGP_EINVAL;
+  *out = nullptr;
+  if (g->num_vertices < 1 || g->num_edges < 0 || !g->indptr || (g->num_edges > 0 && !g->indices)) return LGP_EINVAL;
+  if (g->indptr_bytes != 4 && g->indptr_bytes != 8) return LGP_EINVAL;
+  if (g->num_vertices >= (int64_t(1) << 31)) return LGP_EUNSUPPORTED;
+  if (g->features && (g->feat_dim < 1 || g->elem_bytes < 1)) return LGP_EINVAL;
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess || device < 0 || device >= n_dev) {
+    (void)hipGetLastError();
+    return LGP_EINVAL;
+  }
+  lgp_ctx* c = new (std::nothrow) lgp_ctx();
+  if (!c) return LGP_ENOMEM;
+  int st = LGP_OK;
+  auto bail = [&](int status) {
+    lgp_destroy(c);
+    return status;
+  };
+  if (hipSetDevice(device) != hipSuccess) return bail(LGP_EHIP);
+  c->di.device = device;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, device) == hipSuccess) c->di.num_cus = prop.multiProcessorCount;
+  c->g = *g;
+  const void* p = nullptr;
+  if ((st = device_visible(c, g->indptr, &p, "indptr")) != LGP_OK) return bail(st);
+  c->g.indptr = p;
+  if (g->indices) {
+    if ((st = device_visible(c, g->indices, &p, "indices")) != LGP_OK) return bail(st);
+    c->g.indices = static_cast<const int32_t*>(p);
+  }
+  if (g->features) {
+    if ((st = device_visible(c, g->features, &p, "features")) != LGP_OK) return bail(st);
+    c->g.features = p;
+    c->row_bytes = int64_t(g->feat_dim) * g->elem_bytes;
+    // the row gather divides by the chunk count with a 32-bit reciprocal (<= 4096 chunks per row)
+    const uintptr_t a = uintptr_t(p) | uintptr_t(c->row_bytes);
+    const int64_t vec = (a & 15u) == 0 ? 16 : (a & 7u) == 0 ? 8 : (a & 3u) == 0 ? 4 : (a & 1u) == 0 ? 2 : 0;
+    if (vec == 0 || c->row_bytes / vec > 4096) return bail(LGP_EUNSUPPORTED);
+  }
+  const int64_t V = g->num_vertices;
+  c->n_chunks = (V + kChunkBits - 1) / kChunkBits;
+  const size_t words = size_t(c->n_chunks) * size_t(kChunkWords);
+  hipError_t e = hipSuccess;
+  auto step = [&](hipError_t r) {
+    if (e == hipSuccess) e = r;
+  };
+  step(dev_alloc(&c->t_remap, size_t(V)));
+  step(dev_alloc(&c->f_remap, size_t(V)));
+  step(dev_alloc(&c->topo_hot, size_t(V)));
+  step(dev_alloc(&c->feat_hot, size_t(V)));
+  step(dev_alloc(&c->fbits, words));
+  step(dev_alloc(&c->gbits, words));
+  step(dev_alloc(&c->chunk_counts, size_t(c->n_chunks)));
+  step(dev_alloc(&c->d_err, 1));
+  step(dev_alloc(&c->counters, 2));
+  step(dev_alloc(&c->hs_n, LGP_MAX_HOPS));
+  if (e == hipSuccess) e = hipMemset(c->t_remap, 0xff, sizeof(int32_t) * size_t(V));
+  if (e == hipSuccess) e = hipMemset(c->f_remap, 0xff, sizeof(int32_t) * size_t(V));
+  if (e == hipSuccess) e = hipMemset(c->topo_hot, 0, sizeof(uint32_t) * size_t(V));
+  if (e == hipSuccess) e = hipMemset(c->feat_hot, 0, sizeof(uint32_t) * size_t(V));
+  if (e == hipSuccess) e = hipMemset(c->fbits, 0, sizeof(uint64_t) * words);
+  if (e == hipSuccess) e = hipMemset(c->gbits, 0, sizeof(uint64_t) * words);
+  if (e == hipSuccess) e = hipMemset(c->d_err, 0, sizeof(uint32_t));
+  if (e == hipSuccess) e = hipMemset(c->counters, 0, 2 * sizeof(int32_t));
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->miss_stream, hipStreamNonBlocking);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming);
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return bail(e == hipErrorOutOfMemory ? LGP_ENOMEM : LGP_EHIP);
+  }
+  *out = c;
+  return LGP_OK;
+}
+
+int lgp_destroy(lgp_ctx* c) {
+  if (!c) return LGP_OK;
+  (void)hipSetDevice(c->di.device);
+  (void)hipDeviceSynchronize();
+  free_cache(c);
+  void* ptrs[] = {c->t_remap, c->f_remap, c->topo_hot, c->feat_hot, c->fbits, c->gbits, c->chunk_counts,
+                  c->d_err,   c->counters, c->order_t, c->order_f,  c->lists, c->hs_n};
+  for (void* p : ptrs)
+    if (p) (void)hipFree(p);
+  for (int h = 0; h < LGP_MAX_HOPS; ++h)
+    if (c->hs_frontier[h]) (void)hipFree(c->hs_frontier[h]);
+  for (auto* v : {&c->ev_used, &c->ev_free})
+    for (EvPair& p : *v) {
+      (void)hipEventDestroy(p.a);
+      (void)hipEventDestroy(p.b);
+    }
+  if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+  if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+  if (c->miss_stream) (void)hipStreamDestroy(c->miss_stream);
+  (void)hipGetLastError();
+  delete c;
+  return LGP_OK;
+}
+
+int lgp_build_hotness(lgp_ctx* c, const int32_t* train_ids, int64_t n_train, int32_t batch, const int32_t* fanouts,
+                      int32_t n_hops, uint64_t base_seed, int64_t max_batches, void* stream) {
+  if (!c) return LGP_EINVAL;
+  if (!train_ids || n_train < 0 || batch < 1) return fail(c, LGP_EINVAL, "train_ids / n_train / batch");
+  int st = check_fanouts(c, fanouts, n_hops);
+  if (st != LGP_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  LGP_HIP(c, hipSetDevice(c->di.device));
+  const int64_t V = c->g.num_vertices;
+  int64_t need[LGP_MAX_HOPS], gather_need;
+  worst_case(c, std::min<int64_t>(batch, std::max<int64_t>(n_train, 1)), fanouts, n_hops, need, &gather_need);
+  for (int h = 1; h < n_hops; ++h) {
+    if (c->hs_cap[h] < need[h]) {
+      LGP_HIP(c, hipStreamSynchronize(s));
+      if (c->hs_frontier[h]) (void)hipFree(c->hs_frontier[h]);
+      c->hs_frontier[h] = nullptr;
+      c->hs_cap[h] = 0;
+      LGP_HIP(c, dev_alloc(&c->hs_frontier[h], size_t(need[h])));
+      c->hs_cap[h] = need[h];
+    }
+  }
+  launch_fill_i32(c->di, reinterpret_cast<int32_t*>(c->topo_hot), V, 0, s);
+  launch_fill_i32(c->di, reinterpret_cast<int32_t*>(c->feat_hot), V, 0, s);
+  int64_t n_batches = (n_train + batch - 1) / batch;
+  if (max_batches >= 0 && max_batches < n_batches) n_batches = max_batches;
+  for (int64_t b = 0; b < n_batches; ++b) {
+    const int64_t lo = b * batch;
+    const int32_t nb = int32_t(std::min<int64_t>(batch, n_train - lo));
+    st = sample_core(c, train_ids + lo, nb, fanouts, n_hops, base_seed + uint64_t(b), nullptr, s);
+    if (st != LGP_OK) return st;
+  }
+  c->have_hot = true;
+  return LGP_OK;
+}
+
+int lgp_get_hotness(lgp_ctx* c, uint32_t* topo_hot, uint32_t* feat_hot) {
+  if (!c) return LGP_EINVAL;
+  LGP_HIP(c, hipSetDevice(c->di.device));
+  LGP_HIP(c, hipDeviceSynchronize());
+  const size_t bytes = sizeof(uint32_t) * size_t(c->g.num_vertices);
+  if (topo_hot) LGP_HIP(c, hipMemcpy(topo_hot, c->topo_hot, bytes, hipMemcpyDeviceToHost));
+  if (feat_hot) LGP_HIP(c, hipMemcpy(feat_hot, c->feat_hot, bytes, hipMemcpyDeviceToHost));
+  return LGP_OK;
+}
+
+int lgp_set_hotness(lgp_ctx* c, const uint32_t* topo_hot, const uint32_t* feat_hot) {
+  if (!c) return LGP_EINVAL;
+  LGP_HIP(c, hipSetDevice(c->di.device));
+  LGP_HIP(c, hipDeviceSynchronize());
+  const size_t bytes = sizeof(uint32_t) * size_t(c->g.num_vertices);
+  if (topo_hot) LGP_HIP(c, hipMemcpy(c->topo_hot, topo_hot, bytes, hipMemcpyHostToDevice));
+  if (feat_hot) LGP_HIP(c, hipMemcpy(c->feat_hot, feat_hot, bytes, hipMemcpyHostToDevice));
+  c->have_hot = true;
+  return LGP_OK;
+}
+
+int lgp_plan_cache(lgp_ctx* c, uint64_t topo_budget, uint64_t feat_budget, lgp_cache_plan* plan, void* stream) {
+  if (!c) return LGP_EINVAL;
+  if (!plan) return fail(c, LGP_EINVAL, "plan is null");
+  LGP_HIP(c, hipSetDevice(c->di.device));
+  if (c->plan.n_topo > 0 || c->plan.n_feat > 0)
+    return fail(c, LGP_ESTATE, "lgp_plan_cache re-ranks the vertices; call it before lgp_build_cache");
+  CachePlan p;
+  int st = plan_core(c, topo_budget, feat_budget, &p, nullptr, static_cast<hipStream_t>(stream));
+  if (st != LGP_OK) return st;
+  plan->n_topo = p.n_topo;
+  plan->topo_edges = p.topo_edges;
+  plan->topo_bytes = p.topo_bytes;
+  plan->n_feat = p.n_feat;
+  plan->feat_bytes = p.feat_bytes;
+  return LGP_OK;
+}
+
+int lgp_build_cache(lgp_ctx* c, uint64_t topo_budget, uint64_t feat_budget, void* stream) {
+  if (!c) return LGP_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  LGP_HIP(c, hipSetDevice(c->di.device));
+  const int64_t V = c->g.num_vertices;
+  if (!c->have_hot) return fail(c, LGP_ESTATE, "no hotness yet: call lgp_build_hotness or lgp_set_hotness first");
+  // drop the old cache first: the remaps must not point into freed memory
+  LGP_HIP(c, hipStreamSynchronize(s));
+  LGP_HIP(c, hipStreamSynchronize(c->miss_stream));
+  free_cache(c);
+  launch_fill_i32(c->di, c->t_remap, V, -1, s);
+  launch_fill_i32(c->di, c->f_remap, V, -1, s);
+  CachePlan p;
+  uint64_t* scan = nullptr;
+  int st = plan_core(c, topo_budget, feat_budget, &p, &scan, s);
+  if (st != LGP_OK) return st;
+  hipError_t e = dev_alloc(&c->t_indptr, size_t(p.n_topo + 1));
+  if (e == hipSuccess) e = dev_alloc(&c->t_indices, size_t(p.topo_edges));
+  if (e == hipSuccess && p.n_feat > 0) e = hipMalloc(&c->fc, size_t(p.feat_bytes));
+  if (e == hipSuccess) {
+    launch_topo_offsets(c->di, scan, p.n_topo, c->t_indptr, s);
+    launch_fill_topo(c->di, c->g.indptr, c->g.indptr_bytes, c->g.indices, c->order_t, p.n_topo, c->t_indptr,
+                     c->t_indices, s);
+    launch_scatter_rank(c->di, c->order_t, p.n_topo, c->t_remap, s);
+    if (p.n_feat > 0) {
+      launch_gather_rows(c->di, c->g.features, c->fc, c->row_bytes, nullptr, c->order_f, p.n_feat, nullptr, true, s);
+      launch_scatter_rank(c->di, c->order_f, p.n_feat, c->f_remap, s);
+    }
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  (void)hipFree(scan);
+  if (e != hipSuccess) {
+    st = fail_hip(c, e, "cache fill");
+    free_cache(c);
+    (void)hipMemset(c->t_remap, 0xff, sizeof(int32_t) * size_t(V));
+    (void)hipMemset(c->f_remap, 0xff, sizeof(int32_t) * size_t(V));
+    return st;
+  }
+  c->plan = p;
+  return LGP_OK;
+}
+
+int lgp_get_cache_plan(lgp_ctx* c, lgp_cache_plan* plan) {
+  if (!c) return LGP_EINVAL;
+  if (!plan) return fail(c, LGP_EINVAL, "plan is null");
+  plan->n_topo = c->plan.n_topo;
+  plan->topo_edges = c->plan.topo_edges;
+  plan->topo_bytes = c->plan.topo_bytes;
+  plan->n_feat = c->plan.n_feat;
+  plan->feat_bytes = c->plan.feat_bytes;
+  return LGP_OK;
+}
+
+int lgp_get_cache(lgp_ctx* c, int32_t* topo_ids, int64_t* t_indptr, int32_t* t_indices, int32_t* feat_ids,
+                  void* feat_rows) {
+  if (!c) return LGP_EINVAL;
+  LGP_HIP(c, hipSetDevice(c->di.device));
+  LGP_HIP(c, hipDeviceSynchronize());
+  const CachePlan& p = c->plan;
+  if (topo_ids && p.n_topo)
+    LGP_HIP(c, hipMemcpy(topo_ids, c->order_t, sizeof(int32_t) * size_t(p.n_topo), hipMemcpyDeviceToHost));
+  if (t_indptr) {
+    if (c->t_indptr)
+      LGP_HIP(c, hipMemcpy(t_indptr, c->t_indptr, sizeof(int64_t) * size_t(p.n_topo + 1), hipMemcpyDeviceToHost));
+    else
+      t_indptr[0] = 0;
+  }
+  if (t_indices && p.topo_edges)
+    LGP_HIP(c, hipMemcpy(t_indices, c->t_indices, sizeof(int32_t) * size_t(p.topo_edges), hipMemcpyDeviceToHost));
+  if (feat_ids && p.n_feat)
+    LGP_HIP(c, hipMemcpy(feat_ids, c->order_f, sizeof(int32_t) * size_t(p.n_feat), hipMemcpyDeviceToHost));
+  if (feat_rows && p.n_feat) LGP_HIP(c, hipMemcpy(feat_rows, c->fc, size_t(p.feat_bytes), hipMemcpyDeviceToHost));
+  return LGP_OK;
+}
+
+int lgp_sample_khop(lgp_ctx* c, const int32_t* seeds, int32_t n_seeds, const int32_t* fanouts, int32_t n_hops,
+                    uint64_t rng_seed, const lgp_sample_out* out, void* stream) {
+  if (!c) return LGP_EINVAL;
+  if (n_seeds < 0 || (n_seeds > 0 && !seeds) || !out) return fail(c, LGP_EINVAL, "seeds / n_seeds / out");
+  int st = check_fanouts(c, fanouts, n_hops);
+  if (st != LGP_OK) return st;
+  if (!out->n_frontier || !out->n_gather) return fail(c, LGP_EINVAL, "out has null count pointers");
+  int64_t need[LGP_MAX_HOPS], gather_need;
+  worst_case(c, n_seeds, fanouts, n_hops, need, &gather_need);
+  for (int h = 0; h < n_hops; ++h) {
+    if (need[h] > 0 && (!out->nbr[h] || !out->cnt[h] || (h > 0 && !out->frontier[h])))
+      return fail(c, LGP_EINVAL, "out has a null hop buffer");
+    if (out->cap[h] < need[h]) return fail(c, LGP_ECAPACITY, "out->cap[h] is below the worst-case frontier size");
+  }
+  if (out->gather_cap < gather_need) return fail(c, LGP_ECAPACITY, "out->gather_cap is below the worst case");
+  if (gather_need > 0 && !out->gather_ids) return fail(c, LGP_EINVAL, "out->gather_ids is null");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  LGP_HIP(c, hipSetDevice(c->di.device));
+  EvPair ev = prof_begin(c, PK_SAMPLE, s);
+  st = sample_core(c, seeds, n_seeds, fanouts, n_hops, rng_seed, out, s);
+  prof_end(c, ev, s);
+  return st;
+}
+
+int lgp_gather_features(lgp_ctx* c, const int32_t* ids, int64_t n_max, const int32_t* n_dev, void* out,
+                        int32_t* stats, void* stream) {
+  if (!c) return LGP_EINVAL;
+  if (n_max < 0 || (n_max > 0 && (!ids || !out))) return fail(c, LGP_EINVAL, "ids / out / n_max");
+  if (!c->g.features) return fail(c, LGP_ESTATE, "the graph was created without a feature table");
+  if (n_max >= (int64_t(1) << 31)) return fail(c, LGP_EUNSUPPORTED, "more than 2^31 - 1 rows in one call");
+  const uintptr_t a = uintptr_t(out) | uintptr_t(c->row_bytes);
+  const int64_t vec = (a & 15u) == 0 ? 16 : (a & 7u) == 0 ? 8 : (a & 3u) == 0 ? 4 : (a & 1u) == 0 ? 2 : 0;
+  if (vec == 0 || c->row_bytes / vec > 4096) return fail(c, LGP_EUNSUPPORTED, "output alignment too small for this row width");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  LGP_HIP(c, hipSetDevice(c->di.device));
+  if (n_max > c->list_cap) {
+    LGP_HIP(c, hipStreamSynchronize(s));
+    LGP_HIP(c, hipStreamSynchronize(c->miss_stream));
+    if (c->lists) (void)hipFree(c->lists);
+    c->lists = nullptr;
+    c->list_cap = 0;
+    LGP_HIP(c, dev_alloc(&c->lists, size_t(n_max) * 4));
+    c->list_cap = n_max;
+  }
+  int32_t* counters = stats ? stats : c->counters;
+  if (n_max == 0) {
+    launch_partition(c->di, ids, 0, nullptr, c->f_remap, c->g.num_vertices, nullptr, nullptr, nullptr, nullptr,
+                     counters, c->d_err, s);
+    return LGP_OK;
+  }
+  int32_t* hit_row = c->lists;
+  int32_t* hit_src = c->lists + c->list_cap;
+  int32_t* miss_row = c->lists + 2 * c->list_cap;
+  int32_t* miss_src = c->lists + 3 * c->list_cap;
+  EvPair ev = prof_begin(c, PK_PARTITION, s);
+  launch_partition(c->di, ids, n_max, n_dev, c->f_remap, c->g.num_vertices, hit_row, hit_src, miss_row, miss_src,
+                   counters, c->d_err, s);
+  prof_end(c, ev, s);
+  // fork: misses stream in over PCIe on their own stream while hits run HBM -> HBM
+  LGP_HIP(c, hipEventRecord(c->ev_fork, s));
+  LGP_HIP(c, hipStreamWaitEvent(c->miss_stream, c->ev_fork, 0));
+  if (c->plan.n_feat < c->g.num_vertices) {
+    ev = prof_begin(c, PK_MISS, c->miss_stream);
+    launch_gather_rows(c->di, c->g.features, out, c->row_bytes, miss_row, miss_src, n_max, counters + 1, true,
+                       c->miss_stream);
+    prof_end(c, ev, c->miss_stream);
+  }
+  if (c->plan.n_feat > 0) {
+    ev = prof_begin(c, PK_HIT, s);
+    launch_gather_rows(c->di, c->fc, out, c->row_bytes, hit_row, hit_src, n_max, counters, false, s);
+    prof_end(c, ev, s);
+  }
+  LGP_HIP(c, hipEventRecord(c->ev_join, c->miss_stream));
+  LGP_HIP(c, hipStreamWaitEvent(s, c->ev_join, 0));
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail_hip(c, e, "gather kernel launch");
+  return LGP_OK;
+}
+
+int lgp_check(lgp_ctx* c, void* stream) {
+  if (!c) return LGP_EINVAL;
+  LGP_HIP(c, hipSetDevice(c->di.device));
+  LGP_HIP(c, hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+  LGP_HIP(c, hipStreamSynchronize(c->miss_stream));
+  uint32_t flag = 0;
+  LGP_HIP(c, hipMemcpy(&flag, c->d_err, sizeof(flag), hipMemcpyDeviceToHost));
+  if (flag) {
+    LGP_HIP(c, hipMemset(c->d_err, 0, sizeof(uint32_t)));
+    char buf[96];
+    std::snprintf(buf, sizeof(buf), "device error flag 0x%x (1 = invalid vertex id, 2 = output overrun)", flag);
+    return fail(c, LGP_EDEVICE, buf);
+  }
+  return LGP_OK;
+}
+
+int lgp_set_profiling(lgp_ctx* c, int enable) {
+  if (!c) return LGP_EINVAL;
+  c->profiling = enable != 0;
+  return LGP_OK;
+}
+
+int lgp_get_profile(lgp_ctx* c, lgp_profile* out) {
+  if (!c) return LGP_EINVAL;
+  if (!out) return fail(c, LGP_EINVAL, "out is null");
+  LGP_HIP(c, hipSetDevice(c->di.device));
+  std::memset(out, 0, sizeof(*out));
+  int64_t* counts[PK_COUNT] = {&out->n_sample, &out->n_partition, &out->n_hit, &out->n_miss};
+  double* sums[PK_COUNT] = {&out->ms_sample, &out->ms_partition, &out->ms_hit, &out->ms_miss};
+  for (EvPair& p : c->ev_used) {
+    LGP_HIP(c, hipEventSynchronize(p.b));
+    float ms = 0.f;
+    LGP_HIP(c, hipEventElapsedTime(&ms, p.a, p.b));
+    *counts[p.kind] += 1;
+    *sums[p.kind] += double(ms);
+    c->ev_free.push_back(p);
+  }
+  c->ev_used.clear();
+  return LGP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,161 @@
+// Cache candidate selection and fill-up (Sec. 4.2.2 steps S2-S3).  With one GPU per
+// clique Algorithm 1 reduces to ranking the vertices by descending hotness; the size
+// rules are Eq. 3 (topology) and Eq. 6 (features), evaluated with an inclusive scan
+// along the ranking and a binary search for the budget, as in Sec. 4.3.3.  This is
+// one-off set-up work: the sort and the scan are rocPRIM device primitives, the rest
+// are small kernels.
+#include "common.hpp"
+
+#include <cstring>
+
+#include <rocprim/rocprim.hpp>
+
+namespace lgp {
+namespace {
+
+struct TopoCost {
+  const int32_t* deg;
+  const int32_t* order;
+  __host__ __device__ uint64_t operator()(int64_t r) const { return uint64_t(deg[order[r]]) * 4u + 8u; }
+};
+
+template <typename IdxT>
+__global__ void degrees_kernel(const IdxT* __restrict__ indptr, int64_t num_vertices, int32_t* __restrict__ deg) {
+  for (int64_t v = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; v < num_vertices;
+       v += int64_t(gridDim.x) * blockDim.x)
+    deg[v] = int32_t(indptr[v + 1] - indptr[v]);
+}
+
+__global__ void prefix_within_budget_kernel(const uint64_t* __restrict__ scan, int64_t n, uint64_t budget,
+                                            uint64_t* __restrict__ result) {
+  if (blockIdx.x != 0 || threadIdx.x != 0) return;
+  int64_t lo = 0, hi = n;                       // first index with scan[idx] > budget
+  while (lo < hi) {
+    const int64_t mid = lo + (hi - lo) / 2;
+    if (scan[mid] <= budget) lo = mid + 1;
+    else hi = mid;
+  }
+  result[0] = uint64_t(lo);
+  result[1] = lo > 0 ? scan[lo - 1] : 0;
+}
+
+__global__ void topo_offsets_kernel(const uint64_t* __restrict__ cost_scan, int64_t n_topo,
+                                    int64_t* __restrict__ t_indptr) {
+  for (int64_t r = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; r <= n_topo;
+       r += int64_t(gridDim.x) * blockDim.x)
+    t_indptr[r] = r == 0 ? 0 : int64_t((cost_scan[r - 1] - 8u * uint64_t(r)) / 4u);   // undo Eq. 3's +8 per row
+}
+
+// 16 lanes per cached row: rows average a few dozen ids, hubs just take more passes.
+template <typename IdxT>
+__global__ __launch_bounds__(256) void fill_topo_kernel(const IdxT* __restrict__ h_indptr,
+                                                        const int32_t* __restrict__ h_indices,
+                                                        const int32_t* __restrict__ order, int64_t n_topo,
+                                                        const int64_t* __restrict__ t_indptr,
+                                                        int32_t* __restrict__ t_indices) {
+  const int sub = threadIdx.x & 15;
+  for (int64_t r = (int64_t(blockIdx.x) * 256 + threadIdx.x) >> 4; r < n_topo; r += (int64_t(gridDim.x) * 256) >> 4) {
+    const int32_t v = order[r];
+    const int64_t s = int64_t(h_indptr[v]);
+    const int64_t d = int64_t(h_indptr[int64_t(v) + 1]) - s;
+    const int64_t dst = t_indptr[r];
+    for (int64_t k = sub; k < d; k += 16) t_indices[dst + k] = __builtin_nontemporal_load(h_indices + s + k);
+  }
+}
+
+__global__ void fill_i32_kernel(int32_t* __restrict__ p, int64_t n, int32_t value) {
+  for (int64_t k = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; k < n; k += int64_t(gridDim.x) * blockDim.x)
+    p[k] = value;
+}
+
+__global__ void scatter_rank_kernel(const int32_t* __restrict__ order, int64_t n, int32_t* __restrict__ remap) {
+  for (int64_t r = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; r < n; r += int64_t(gridDim.x) * blockDim.x)
+    remap[order[r]] = int32_t(r);
+}
+
+inline unsigned grid_for(const DeviceInfo& di, int64_t n, int per_block = 256) {
+  int64_t blocks = (n + per_block - 1) / per_block;
+  const int64_t full = int64_t(di.num_cus) * 8;
+  if (blocks > full) blocks = full;
+  if (blocks < 1) blocks = 1;
+  return unsigned(blocks);
+}
+
+}  // namespace
+
+hipError_t rank_by_hotness(const uint32_t* hot, int64_t num_vertices, int32_t* order, hipStream_t s) {
+  uint32_t* keys_out = nullptr;
+  void* temp = nullptr;
+  size_t temp_bytes = 0;
+  hipError_t e = hipMalloc(&keys_out, sizeof(uint32_t) * size_t(num_vertices));
+  if (e != hipSuccess) return e;
+  rocprim::counting_iterator<int32_t> ids(0);
+  // Stable descending radix sort: equal hotness keeps ascending id order.
+  e = rocprim::radix_sort_pairs_desc(nullptr, temp_bytes, hot, keys_out, ids, order, size_t(num_vertices), 0, 32, s);
+  if (e == hipSuccess) e = hipMalloc(&temp, temp_bytes ? temp_bytes : 16);
+  if (e == hipSuccess)
+    e = rocprim::radix_sort_pairs_desc(temp, temp_bytes, hot, keys_out, ids, order, size_t(num_vertices), 0, 32, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (temp) (void)hipFree(temp);
+  (void)hipFree(keys_out);
+  return e;
+}
+
+void launch_degrees(const DeviceInfo& di, const void* h_indptr, int32_t indptr_bytes, int64_t num_vertices,
+                    int32_t* deg, hipStream_t s) {
+  if (indptr_bytes == 8)
+    hipLaunchKernelGGL(degrees_kernel<int64_t>, dim3(grid_for(di, num_vertices)), dim3(256), 0, s,
+                       static_cast<const int64_t*>(h_indptr), num_vertices, deg);
+  else
+    hipLaunchKernelGGL(degrees_kernel<int32_t>, dim3(grid_for(di, num_vertices)), dim3(256), 0, s,
+                       static_cast<const int32_t*>(h_indptr), num_vertices, deg);
+}
+
+hipError_t scan_topo_cost(const int32_t* deg, const int32_t* order, int64_t num_vertices, uint64_t* cost_scan,
+                          hipStream_t s) {
+  auto in = rocprim::make_transform_iterator(rocprim::counting_iterator<int64_t>(0), TopoCost{deg, order});
+  void* temp = nullptr;
+  size_t temp_bytes = 0;
+  hipError_t e = rocprim::inclusive_scan(nullptr, temp_bytes, in, cost_scan, size_t(num_vertices),
+                                         rocprim::plus<uint64_t>(), s);
+  if (e == hipSuccess) e = hipMalloc(&temp, temp_bytes ? temp_bytes : 16);
+  if (e == hipSuccess)
+    e = rocprim::inclusive_scan(temp, temp_bytes, in, cost_scan, size_t(num_vertices), rocprim::plus<uint64_t>(), s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (temp) (void)hipFree(temp);
+  return e;
+}
+
+void launch_prefix_within_budget(const uint64_t* scan, int64_t n, uint64_t budget, uint64_t* result, hipStream_t s) {
+  hipLaunchKernelGGL(prefix_within_budget_kernel, dim3(1), dim3(64), 0, s, scan, n, budget, result);
+}
+
+void launch_topo_offsets(const DeviceInfo& di, const uint64_t* cost_scan, int64_t n_topo, int64_t* t_indptr,
+                         hipStream_t s) {
+  hipLaunchKernelGGL(topo_offsets_kernel, dim3(grid_for(di, n_topo + 1)), dim3(256), 0, s, cost_scan, n_topo,
+                     t_indptr);
+}
+
+void launch_fill_topo(const DeviceInfo& di, const void* h_indptr, int32_t indptr_bytes, const int32_t* h_indices,
+                      const int32_t* order, int64_t n_topo, const int64_t* t_indptr, int32_t* t_indices,
+                      hipStream_t s) {
+  if (n_topo <= 0) return;
+  const unsigned grid = grid_for(di, n_topo, 16);
+  if (indptr_bytes == 8)
+    hipLaunchKernelGGL(fill_topo_kernel<int64_t>, dim3(grid), dim3(256), 0, s, static_cast<const int64_t*>(h_indptr),
+                       h_indices, order, n_topo, t_indptr, t_indices);
+  else
+    hipLaunchKernelGGL(fill_topo_kernel<int32_t>, dim3(grid), dim3(256), 0, s, static_cast<const int32_t*>(h_indptr),
+                       h_indices, order, n_topo, t_indptr, t_indices);
+}
+
+void launch_fill_i32(const DeviceInfo& di, int32_t* p, int64_t n, int32_t value, hipStream_t s) {
+  hipLaunchKernelGGL(fill_i32_kernel, dim3(grid_for(di, n)), dim3(256), 0, s, p, n, value);
+}
+
+void launch_scatter_rank(const DeviceInfo& di, const int32_t* order, int64_t n, int32_t* remap, hipStream_t s) {
+  if (n <= 0) return;
+  hipLaunchKernelGGL(scatter_rank_kernel, dim3(grid_for(di, n)), dim3(256), 0, s, order, n, remap);
+}
+
+}  // namespace lgp

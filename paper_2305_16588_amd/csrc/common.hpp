@@ -1,0 +1,101 @@
+// Internal declarations shared by the translation units of liblegion_prep.
+// Host-side launchers only; kernels live in the .hip files.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "legion_prep.h"
+
+namespace lgp {
+
+// Device-side error bits (sticky, OR-ed into ctx->d_err).
+enum : uint32_t { ERR_BAD_ID = 1u, ERR_OVERRUN = 2u };
+
+// One dedup bitmap chunk = what one workgroup of the compaction kernels covers.
+constexpr int kCompactThreads = 256;
+constexpr int kWordsPerThread = 4;                                   // 64-bit words
+constexpr int64_t kChunkWords = int64_t(kCompactThreads) * kWordsPerThread;
+constexpr int64_t kChunkBits = kChunkWords * 64;                     // 65536 vertices per workgroup
+
+struct DeviceInfo {
+  int device = 0;
+  int num_cus = 256;
+};
+
+// Pointers every sampling kernel needs.
+struct TopoView {
+  const void* h_indptr;      // CPU-resident CSR (GPU-addressable)
+  const int32_t* h_indices;
+  const int32_t* t_remap;    // vertex -> topology-cache slot, -1 if absent; nullptr = ignore the cache
+  const int64_t* t_indptr;   // cached CSR (HBM)
+  const int32_t* t_indices;
+  int32_t indptr_bytes;
+  int64_t num_vertices;
+};
+
+// ---- sampler.hip ----------------------------------------------------------
+// Expand frontier[0 .. *n_frontier) with fan-out f at hop `hop`.  Writes nbr / cnt
+// (either may be null), sets the bit of every sampled neighbour in `mark_bits`,
+// adds cnt to topo_hot[v] if topo_hot is given.
+void launch_sample_hop(const DeviceInfo& di, const TopoView& tv, const int32_t* frontier, const int32_t* n_frontier,
+                       int64_t cap, int32_t fanout, int32_t hop, uint64_t rng_seed, int32_t* nbr, int32_t* cnt,
+                       uint32_t* mark_bits, uint32_t* topo_hot, uint32_t* d_err, hipStream_t s);
+// Set the bit of every id in ids[0 .. n) and store n to *n_out (if given).
+void launch_mark_ids(const DeviceInfo& di, const int32_t* ids, int32_t n, int64_t num_vertices, uint32_t* bits,
+                     int32_t* n_out, uint32_t* d_err, hipStream_t s);
+
+// ---- compact.hip ----------------------------------------------------------
+// Turn the bitmap `bits` (n_chunks * kChunkWords 64-bit words) into the ascending id
+// list out[0 .. *n_out).  If or_into is given, bits are OR-ed into it; `bits` is
+// cleared.  If bump is given, bump[id] += 1 for every set bit.  With n_out == nullptr no
+// list is produced: only the OR / clear / bump side effects happen.
+void launch_compact(const DeviceInfo& di, uint64_t* bits, uint64_t* or_into, int64_t n_chunks, int32_t* chunk_counts,
+                    int32_t* out, int64_t out_cap, int32_t* n_out, uint32_t* bump, uint32_t* d_err, hipStream_t s);
+
+// ---- gather.hip -----------------------------------------------------------
+// Look up every id in the feature remap and append (row, slot) to the hit list or
+// (row, id) to the miss list.  counters[0] = hits, counters[1] = misses (zeroed here).
+void launch_partition(const DeviceInfo& di, const int32_t* ids, int64_t n_max, const int32_t* n_dev,
+                      const int32_t* f_remap, int64_t num_vertices, int32_t* hit_row, int32_t* hit_src,
+                      int32_t* miss_row, int32_t* miss_src, int32_t* counters, uint32_t* d_err, hipStream_t s);
+// dst[row[e], :] = src[srcrow[e], :] for e < *n_dev (or n_max if n_dev is null); rows are
+// row_bytes wide; `row` may be null (row = e).  streaming = source is read once over
+// PCIe (non-temporal loads).
+void launch_gather_rows(const DeviceInfo& di, const void* src, void* dst, int64_t row_bytes, const int32_t* row,
+                        const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, bool streaming, hipStream_t s);
+void launch_copy_i32(const int32_t* src, int32_t* dst, int n, hipStream_t s);
+
+// ---- cache.hip ------------------------------------------------------------
+struct CachePlan {
+  int64_t n_topo = 0, topo_edges = 0, n_feat = 0;
+  uint64_t topo_bytes = 0, feat_bytes = 0;
+};
+struct RankScratch;  // opaque, owned by cache.hip
+// Rank vertices by (hotness descending, id ascending) into order[V].  Synchronous parts
+// use `s`.  Returns hipSuccess or the failing HIP status.
+hipError_t rank_by_hotness(const uint32_t* hot, int64_t num_vertices, int32_t* order, hipStream_t s);
+// deg[v] = indptr[v + 1] - indptr[v], streamed from CPU memory.
+void launch_degrees(const DeviceInfo& di, const void* h_indptr, int32_t indptr_bytes, int64_t num_vertices,
+                    int32_t* deg, hipStream_t s);
+// Inclusive scan of the Eq. 3 cost (deg * 4 + 8) along `order`; cost_scan has V entries.
+hipError_t scan_topo_cost(const int32_t* deg, const int32_t* order, int64_t num_vertices, uint64_t* cost_scan,
+                          hipStream_t s);
+// result[0] = number of entries of the ascending array scan[0..n) that are <= budget,
+// result[1] = scan[that - 1] (0 if none).  Device-side binary search.
+void launch_prefix_within_budget(const uint64_t* scan, int64_t n, uint64_t budget, uint64_t* result, hipStream_t s);
+// t_indptr[r] = edges before rank r, r = 0 .. n_topo (derived from the cost scan).
+void launch_topo_offsets(const DeviceInfo& di, const uint64_t* cost_scan, int64_t n_topo, int64_t* t_indptr,
+                         hipStream_t s);
+// Copy the adjacency of order[0 .. n_topo) from CPU memory into the cached CSR.
+void launch_fill_topo(const DeviceInfo& di, const void* h_indptr, int32_t indptr_bytes, const int32_t* h_indices,
+                      const int32_t* order, int64_t n_topo, const int64_t* t_indptr, int32_t* t_indices,
+                      hipStream_t s);
+void launch_fill_i32(const DeviceInfo& di, int32_t* p, int64_t n, int32_t value, hipStream_t s);
+// remap[order[r]] = r for r < n.
+void launch_scatter_rank(const DeviceInfo& di, const int32_t* order, int64_t n, int32_t* remap, hipStream_t s);
+
+}  // namespace lgp

@@ -1,0 +1,154 @@
+// Neighbour sampler (Sec. 2.2 step 2; Sec. 5 "neighbor sampler") for gfx950.
+//
+// A group of P = next_pow2(fanout) lanes owns one frontier vertex; lane i is sample
+// slot i.  Row bounds come from the HBM topology cache when the vertex is cached and
+// from the CPU-resident CSR (read in place over PCIe) otherwise.  All slots draw their
+// Philox number at once; Floyd's sequential "already taken?" test becomes fanout-1
+// group broadcasts.  The kernel is bound by dependent-load latency, so it keeps the
+// register footprint small and the grid at full occupancy.
+#include "common.hpp"
+#include "philox_dev.hpp"
+
+namespace lgp {
+namespace {
+
+template <typename IdxT, int P>
+__global__ __launch_bounds__(256) void sample_hop_kernel(
+    const IdxT* __restrict__ h_indptr, const int32_t* __restrict__ h_indices, const int32_t* __restrict__ t_remap,
+    const int64_t* __restrict__ t_indptr, const int32_t* __restrict__ t_indices, int64_t num_vertices,
+    const int32_t* __restrict__ frontier, const int32_t* __restrict__ n_frontier, int64_t cap, int32_t f, int32_t hop,
+    uint32_t k0, uint32_t k1, int32_t* __restrict__ nbr, int32_t* __restrict__ cnt, uint32_t* __restrict__ mark_bits,
+    uint32_t* __restrict__ topo_hot, uint32_t* __restrict__ d_err) {
+  constexpr int G = 256 / P;                      // vertices per workgroup pass
+  int64_t n = *n_frontier;
+  if (n > cap) n = cap;                           // never trust a count beyond the buffer
+  const int i = threadIdx.x % P;                  // sample slot
+  const int gidx = threadIdx.x / P;
+  for (int64_t base = int64_t(blockIdx.x) * G; base < n; base += int64_t(gridDim.x) * G) {
+    const int64_t g = base + gidx;
+    bool active = g < n;
+    int32_t v = active ? frontier[g] : 0;
+    bool bad = active && (uint32_t(v) >= uint64_t(num_vertices));
+    int64_t s = 0, d64 = 0;
+    const int32_t* colbase = h_indices;
+    if (active && !bad) {
+      const int32_t slot = t_remap ? t_remap[v] : -1;
+      if (slot >= 0) {
+        s = t_indptr[slot];
+        d64 = t_indptr[slot + 1] - s;
+        colbase = t_indices;
+      } else {
+        s = int64_t(h_indptr[v]);
+        d64 = int64_t(h_indptr[int64_t(v) + 1]) - s;
+      }
+      if (d64 < 0 || d64 > 0x7fffffff) { bad = true; d64 = 0; }
+    }
+    if (bad) {
+      if (i == 0) atomicOr(d_err, ERR_BAD_ID);
+      d64 = 0;
+    }
+    const int32_t d = int32_t(d64);
+    const bool big = active && d > f;
+    int32_t p = i;                                 // position inside the row
+    if (__any(big)) {
+      int32_t t = -1, j = 0;
+      if (big && i < f) {
+        j = d - f + i;
+        t = int32_t(__umul64hi(philox_draw64(k0, k1, uint32_t(v), uint32_t(hop), uint32_t(i)), uint64_t(j) + 1));
+      }
+      int32_t pc = t;
+      bool moved = false;
+      for (int k = 0; k + 1 < f; ++k) {            // slot k is final once slots < k are
+        const int32_t pk = __shfl(pc, k, P);
+        if (big && i > k && !moved && t == pk) { pc = j; moved = true; }
+      }
+      if (big) p = pc;
+    }
+    if (active && i < f) {
+      const bool valid = big || i < d;
+      int32_t u = -1;
+      if (valid) {
+        u = colbase[s + p];
+        if (uint32_t(u) >= uint64_t(num_vertices)) {
+          atomicOr(d_err, ERR_BAD_ID);
+          u = -1;
+        } else {
+          atomicOr(&mark_bits[uint32_t(u) >> 5], 1u << (uint32_t(u) & 31u));
+        }
+      }
+      if (nbr) nbr[g * f + i] = u;
+    }
+    if (active && i == 0) {
+      const int32_t c = d < f ? d : f;
+      if (cnt) cnt[g] = c;
+      if (topo_hot && c > 0) atomicAdd(&topo_hot[v], uint32_t(c));
+    }
+  }
+}
+
+__global__ void mark_ids_kernel(const int32_t* __restrict__ ids, int32_t n, int64_t num_vertices,
+                                uint32_t* __restrict__ bits, int32_t* __restrict__ n_out,
+                                uint32_t* __restrict__ d_err) {
+  const int64_t tid = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (tid == 0 && n_out) *n_out = n;
+  for (int64_t k = tid; k < n; k += int64_t(gridDim.x) * blockDim.x) {
+    const int32_t u = ids[k];
+    if (uint32_t(u) >= uint64_t(num_vertices)) atomicOr(d_err, ERR_BAD_ID);
+    else atomicOr(&bits[uint32_t(u) >> 5], 1u << (uint32_t(u) & 31u));
+  }
+}
+
+template <typename IdxT, int P>
+void launch_one(const DeviceInfo& di, const TopoView& tv, const int32_t* frontier, const int32_t* n_frontier,
+                int64_t cap, int32_t f, int32_t hop, uint64_t seed, int32_t* nbr, int32_t* cnt, uint32_t* mark_bits,
+                uint32_t* topo_hot, uint32_t* d_err, hipStream_t s) {
+  constexpr int G = 256 / P;
+  int64_t blocks = (cap + G - 1) / G;
+  const int64_t full = int64_t(di.num_cus) * 8;    // 8 workgroups x 4 waves = 32 waves per CU
+  if (blocks > full) blocks = full;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL((sample_hop_kernel<IdxT, P>), dim3(unsigned(blocks)), dim3(256), 0, s,
+                     static_cast<const IdxT*>(tv.h_indptr), tv.h_indices, tv.t_remap, tv.t_indptr, tv.t_indices,
+                     tv.num_vertices, frontier, n_frontier, cap, f, hop, uint32_t(seed), uint32_t(seed >> 32), nbr,
+                     cnt, mark_bits, topo_hot, d_err);
+}
+
+template <typename IdxT>
+void dispatch_p(int P, const DeviceInfo& di, const TopoView& tv, const int32_t* frontier, const int32_t* n_frontier,
+                int64_t cap, int32_t f, int32_t hop, uint64_t seed, int32_t* nbr, int32_t* cnt, uint32_t* mark_bits,
+                uint32_t* topo_hot, uint32_t* d_err, hipStream_t s) {
+#define LGP_CASE(PP)                                                                                            \
+  case PP:                                                                                                      \
+    launch_one<IdxT, PP>(di, tv, frontier, n_frontier, cap, f, hop, seed, nbr, cnt, mark_bits, topo_hot, d_err, \
+                         s);                                                                                    \
+    break;
+  switch (P) {
+    LGP_CASE(1) LGP_CASE(2) LGP_CASE(4) LGP_CASE(8) LGP_CASE(16) LGP_CASE(32) LGP_CASE(64)
+  }
+#undef LGP_CASE
+}
+
+}  // namespace
+
+void launch_sample_hop(const DeviceInfo& di, const TopoView& tv, const int32_t* frontier, const int32_t* n_frontier,
+                       int64_t cap, int32_t fanout, int32_t hop, uint64_t rng_seed, int32_t* nbr, int32_t* cnt,
+                       uint32_t* mark_bits, uint32_t* topo_hot, uint32_t* d_err, hipStream_t s) {
+  int P = 1;
+  while (P < fanout) P <<= 1;
+  if (tv.indptr_bytes == 8)
+    dispatch_p<int64_t>(P, di, tv, frontier, n_frontier, cap, fanout, hop, rng_seed, nbr, cnt, mark_bits, topo_hot,
+                        d_err, s);
+  else
+    dispatch_p<int32_t>(P, di, tv, frontier, n_frontier, cap, fanout, hop, rng_seed, nbr, cnt, mark_bits, topo_hot,
+                        d_err, s);
+}
+
+void launch_mark_ids(const DeviceInfo& di, const int32_t* ids, int32_t n, int64_t num_vertices, uint32_t* bits,
+                     int32_t* n_out, uint32_t* d_err, hipStream_t s) {
+  int blocks = (n + 255) / 256;
+  if (blocks > di.num_cus * 4) blocks = di.num_cus * 4;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(mark_ids_kernel, dim3(blocks), dim3(256), 0, s, ids, n, num_vertices, bits, n_out, d_err);
+}
+
+}  // namespace lgp

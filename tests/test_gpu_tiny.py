@@ -1,0 +1,206 @@
+"""GPU parity on the tiny workload (config 1) and on edge cases: every output of the
+HIP path is compared bit for bit with the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import datagen
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def W():
+    from gpu_common import Workload
+    return Workload(datagen.TINY)
+
+
+def test_sampling_every_batch_of_the_epoch(W):
+    from gpu_common import assert_batch_equal
+    import paper_2305_16588_amd as lgp
+    spec = W.spec
+    buf = lgp.SampleBuffers(W.V, spec.batch, spec.fanouts)
+    n_batches = (W.tablet.size + spec.batch - 1) // spec.batch
+    assert n_batches == 10
+    for b in range(n_batches):
+        seeds, seeds_dev = W.batch(b)
+        W.ctx.sample_khop(seeds_dev, spec.fanouts, spec.base_seed + b, out=buf)
+        got = buf.to_host(seeds_dev)
+        ref = W.orc.sample_khop(seeds, spec.fanouts, spec.base_seed + b)
+        assert_batch_equal(ref, got, f"batch {b}")
+    W.ctx.check()
+
+
+@pytest.mark.parametrize("fanouts", [(1,), (64,), (3, 2, 2, 2), (25, 10), (15, 10, 5), (16, 8), (33, 2)])
+def test_sampling_fanout_shapes(W, fanouts):
+    from gpu_common import assert_batch_equal
+    seeds, seeds_dev = W.tablet[:300], W.tablet_dev[:300]
+    buf = W.ctx.sample_khop(seeds_dev, fanouts, 777)
+    assert_batch_equal(W.orc.sample_khop(seeds, fanouts, 777), buf.to_host(seeds_dev), str(fanouts))
+    W.ctx.check()
+
+
+def test_sampling_degenerate_inputs(W):
+    from gpu_common import assert_batch_equal
+    deg = np.diff(W.indptr)
+    iso = np.flatnonzero(deg == 0)[:3].astype(np.int32)
+    hub = np.array([int(np.argmax(deg))], dtype=np.int32)
+    for seeds in (np.empty(0, np.int32), iso, hub, np.concatenate([iso, hub])):
+        dev = torch.from_numpy(seeds).cuda()
+        buf = W.ctx.sample_khop(dev, (10, 5), 2**63 + 11)      # seed with the high word in use
+        assert_batch_equal(W.orc.sample_khop(seeds, (10, 5), 2**63 + 11), buf.to_host(dev), f"seeds {seeds}")
+    W.ctx.check()
+
+
+def test_hotness_whole_epoch(W):
+    spec = W.spec
+    W.ctx.build_hotness(W.tablet_dev, spec.batch, spec.fanouts, spec.base_seed)
+    topo, feat = W.ctx.get_hotness()
+    rt, rf, nb = W.orc.build_hotness(W.tablet, spec.batch, spec.fanouts, spec.base_seed)
+    assert nb == 10 and (topo == rt).all() and (feat == rf).all()
+    W.ctx.build_hotness(W.tablet_dev, spec.batch, spec.fanouts, spec.base_seed, max_batches=3)
+    topo, feat = W.ctx.get_hotness()
+    rt, rf, nb = W.orc.build_hotness(W.tablet, spec.batch, spec.fanouts, spec.base_seed, max_batches=3)
+    assert nb == 3 and (topo == rt).all() and (feat == rf).all()
+    W.ctx.check()
+
+
+def _check_cache(W, topo_budget, feat_budget):
+    plan = W.ctx.build_cache(topo_budget, feat_budget)
+    topo_hot, feat_hot = W.ctx.get_hotness()
+    qt, qf = W.orc.rank_by_hotness(topo_hot), W.orc.rank_by_hotness(feat_hot)
+    n_t, n_f = W.orc.plan_topo(qt, topo_budget), W.orc.plan_feat(feat_budget)
+    assert (plan.n_topo, plan.n_feat) == (n_t, n_f)
+    topo_ids, t_indptr, t_indices, feat_ids, feat_rows = W.ctx.get_cache()
+    r_indptr, r_indices = W.orc.fill_topo(qt, n_t)
+    assert (topo_ids == qt[:n_t]).all() and (feat_ids == qf[:n_f]).all()
+    assert (t_indptr == r_indptr).all() and (t_indices == r_indices).all()
+    assert plan.topo_edges == r_indices.size and plan.topo_bytes == 4 * r_indices.size + 8 * n_t
+    assert feat_rows.tobytes() == W.orc.fill_feat(qf, n_f).tobytes()
+    return plan, qf
+
+
+def test_cache_selection_and_contents(W):
+    spec = W.spec
+    W.ctx.build_hotness(W.tablet_dev, spec.batch, spec.fanouts, spec.base_seed)
+    total_t = 4 * W.E + 8 * W.V
+    tb, fb = datagen.budgets(spec, W.E)
+    for topo_budget, feat_budget in [(tb, fb), (0, 0), (total_t, W.V * 512), (total_t - 1, W.V * 512 - 1), (8, 511),
+                                     (total_t * 3, 10**12), (tb, 0), (0, fb)]:
+        _check_cache(W, topo_budget, feat_budget)
+    W.ctx.check()
+
+
+def test_cache_is_transparent_to_sampling_and_gather(W):
+    from gpu_common import assert_batch_equal
+    spec = W.spec
+    W.ctx.build_hotness(W.tablet_dev, spec.batch, spec.fanouts, spec.base_seed)
+    seeds, seeds_dev = W.batch(2)
+    ref = W.orc.sample_khop(seeds, spec.fanouts, 31337)
+    ref_rows = W.orc.gather(ref.gather_ids)
+    total_t = 4 * W.E + 8 * W.V
+    for topo_frac, feat_frac in [(0.0, 0.0), (0.2, 0.2), (1.0, 1.0), (0.0, 1.0), (1.0, 0.0), (0.5, 0.01)]:
+        plan, qf = _check_cache(W, int(topo_frac * total_t), int(feat_frac * W.V) * 512)
+        buf = W.ctx.sample_khop(seeds_dev, spec.fanouts, 31337)
+        assert_batch_equal(ref, buf.to_host(seeds_dev), f"cache {topo_frac}/{feat_frac}")
+        stats = torch.zeros(2, dtype=torch.int32, device="cuda")
+        rows = W.ctx.gather_features(buf.gather_ids, n_dev=buf.n_gather, stats=stats)
+        n = int(buf.n_gather.item())
+        assert n == ref.gather_ids.size
+        assert rows[:n].cpu().numpy().tobytes() == ref_rows.tobytes()
+        n_hit = W.orc.count_hits(ref.gather_ids, qf, plan.n_feat)
+        assert stats.tolist() == [n_hit, n - n_hit]
+    W.ctx.check()
+
+
+def test_gather_any_id_list(W):
+    spec = W.spec
+    W.ctx.build_hotness(W.tablet_dev, spec.batch, spec.fanouts, spec.base_seed)
+    W.ctx.build_cache(0, 2000 * 512)
+    rng = np.random.default_rng(4)
+    for n in (0, 1, 63, 64, 65, 1000, 4097, 30000):
+        ids = rng.integers(0, W.V, size=n).astype(np.int32)    # duplicates, arbitrary order
+        dev = torch.from_numpy(ids).cuda()
+        rows = W.ctx.gather_features(dev)
+        assert rows.shape == (n, spec.feat_dim)
+        assert rows.cpu().numpy().tobytes() == W.orc.gather(ids).tobytes()
+    W.ctx.check()
+
+
+def test_determinism_same_call_twice(W):
+    spec = W.spec
+    seeds, seeds_dev = W.batch(1)
+    a = W.ctx.sample_khop(seeds_dev, spec.fanouts, 5)
+    b = W.ctx.sample_khop(seeds_dev, spec.fanouts, 5)
+    torch.cuda.synchronize()
+    assert torch.equal(a.n_frontier, b.n_frontier) and torch.equal(a.n_gather, b.n_gather)
+    n = int(a.n_gather.item())
+    assert torch.equal(a.gather_ids[:n], b.gather_ids[:n]) and torch.equal(a.nbr[0], b.nbr[0])
+    ra = W.ctx.gather_features(a.gather_ids[:n].contiguous())
+    rb = W.ctx.gather_features(a.gather_ids[:n].contiguous())
+    assert torch.equal(ra, rb)
+
+
+def test_argument_errors_are_reported_on_the_host(W):
+    import paper_2305_16588_amd as lgp
+    seeds_dev = W.tablet_dev[:100]
+    with pytest.raises(lgp.LegionPrepError) as e:
+        W.ctx.sample_khop(seeds_dev, (65,), 1)
+    assert e.value.status == -4
+    with pytest.raises(lgp.LegionPrepError) as e:
+        W.ctx.sample_khop(seeds_dev, (0,), 1)
+    assert e.value.status == -1
+    small = lgp.SampleBuffers(W.V, 50, (10, 5))
+    with pytest.raises(lgp.LegionPrepError) as e:
+        W.ctx.sample_khop(seeds_dev, (2,) * 9, 1, out=small)   # more hops than LGP_MAX_HOPS
+    assert e.value.status == -4
+    with pytest.raises(lgp.LegionPrepError) as e:
+        W.ctx.sample_khop(seeds_dev, (10, 5), 1, out=small)
+    assert e.value.status == -3
+    fresh = lgp.Context(W.indptr, W.indices, W.features)
+    with pytest.raises(lgp.LegionPrepError) as e:
+        fresh.build_cache(100, 100)
+    assert e.value.status == -2
+    unpinned = np.array(W.indptr)
+    with pytest.raises(lgp.LegionPrepError) as e:
+        lgp.Context(unpinned, W.indices, W.features)
+    assert e.value.status == -1
+    fresh.close()
+
+
+def test_invalid_vertex_id_sets_the_device_flag(W):
+    import paper_2305_16588_amd as lgp
+    bad = torch.tensor([1, W.V, 5], dtype=torch.int32, device="cuda")
+    W.ctx.sample_khop(bad, (3,), 1)
+    with pytest.raises(lgp.LegionPrepError) as e:
+        W.ctx.check()
+    assert e.value.status == -7
+    W.ctx.check()                                              # the flag is cleared once reported
+    W.ctx.gather_features(torch.tensor([-1, 2], dtype=torch.int32, device="cuda"))
+    with pytest.raises(lgp.LegionPrepError):
+        W.ctx.check()
+    # the context keeps working afterwards
+    seeds, seeds_dev = W.batch(0)
+    from gpu_common import assert_batch_equal
+    buf = W.ctx.sample_khop(seeds_dev, (10, 5), 9)
+    assert_batch_equal(W.orc.sample_khop(seeds, (10, 5), 9), buf.to_host(seeds_dev))
+
+
+def test_int64_offsets_and_fp16_rows():
+    from gpu_common import Workload, assert_batch_equal
+    from dataclasses import replace
+    spec = replace(datagen.TINY, name="tiny64", feat_dim=7, feat_dtype="float16", index64=True)
+    Wl = Workload(spec)
+    assert Wl.indptr.dtype == np.int64 and Wl.features.dtype == np.float16
+    seeds, seeds_dev = Wl.batch(0)
+    buf = Wl.ctx.sample_khop(seeds_dev, (10, 5), 3)
+    ref = Wl.orc.sample_khop(seeds, (10, 5), 3)
+    assert_batch_equal(ref, buf.to_host(seeds_dev))
+    Wl.ctx.build_hotness(Wl.tablet_dev, 1024, (10, 5), 1, max_batches=2)
+    Wl.ctx.build_cache(10**6, 14 * 3000)
+    n = int(buf.n_gather.item())
+    rows = Wl.ctx.gather_features(buf.gather_ids, n_dev=buf.n_gather)       # 14-byte rows: 2-byte chunks
+    assert rows[:n].cpu().numpy().tobytes() == Wl.orc.gather(ref.gather_ids).tobytes()
+    buf2 = Wl.ctx.sample_khop(seeds_dev, (10, 5), 3)
+    assert_batch_equal(ref, buf2.to_host(seeds_dev))
+    Wl.ctx.check()
