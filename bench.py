@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the mini-batch data-preparation hot path on one MI355X.
+
+One step = sample_khop + gather_features for one mini-batch of the workload's
+training tablet (all per-batch stages; the caches are built beforehand from a
+pre-sampling epoch, whose time is reported separately).  Inputs are seeded and
+synthetic (see datagen) and are resident -- graph and feature table in pinned CPU
+memory, caches in HBM -- before the timed region starts.
+
+Prints ONE JSON line.  `roofline` covers the cache-hit row gather (HBM -> HBM),
+`roofline_pcie` the miss row gather (CPU memory -> HBM); both use HIP events
+recorded by the library on the streams the kernels run on.  `cpu_baseline` is
+the single-threaded CPU oracle timed on a bounded sample of the same batches.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+PCIE_PEAK_GBS = 63.0           # PCIe Gen5 x16, one direction: 32 GT/s * 16 * 128/130 / 8
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="mid", help="tiny | mid | wide | large | share (optionally name@scale)")
+    ap.add_argument("--feat-frac", type=float, default=None, help="override the feature-cache ratio")
+    ap.add_argument("--topo-frac", type=float, default=None, help="override the topology-cache ratio")
+    ap.add_argument("--overlap", action="store_true", help="miss gather on a second stream beside the hit gather")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-batches", type=int, default=0, help="oracle batches to time (0 = pick for ~15 s)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build covers one GPU's share of the work; --gpus must be 1 "
+              "(no collectives or sharding are part of it)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from dataclasses import replace
+
+    import datagen
+    import paper_2305_16588_amd as lgp
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 3
+
+    name, _, scale = args.workload.partition("@")
+    spec = datagen.WORKLOADS[name]
+    if scale:
+        spec = datagen.scaled(spec, float(scale))
+    if args.feat_frac is not None:
+        spec = replace(spec, feat_frac=args.feat_frac)
+    if args.topo_frac is not None:
+        spec = replace(spec, topo_frac=args.topo_frac)
+
+    t0 = time.time()
+    indptr, indices = datagen.make_graph(spec, device="cuda", indices_alloc=lambda n: lgp.pinned_empty(n, np.int32))
+    indptr = lgp.pinned_copy(indptr)
+    npdt = np.float32 if spec.feat_dtype == "float32" else np.float16
+    feats = lgp.pinned_empty((spec.num_vertices, spec.feat_dim), npdt)
+    datagen.make_features(spec, device="cuda", out=feats)
+    tablet = datagen.make_tablet(spec)
+    t_gen = time.time() - t0
+    V, E, D = spec.num_vertices, int(indices.size), spec.feat_dim
+    row_bytes = D * feats.dtype.itemsize
+
+    ctx = lgp.Context(indptr, indices, feats)
+    ctx.set_overlap(args.overlap)
+    tablet_dev = torch.from_numpy(tablet).cuda()
+    torch.cuda.synchronize()
+    t0 = time.time()
+    ctx.build_hotness(tablet_dev, spec.batch, spec.fanouts, spec.base_seed)
+    torch.cuda.synchronize()
+    t_hot = time.time() - t0
+    topo_b, feat_b = datagen.budgets(spec, E)
+    t0 = time.time()
+    plan = ctx.build_cache(topo_b, feat_b)
+    t_cache = time.time() - t0
+
+    n_batches = (tablet.size + spec.batch - 1) // spec.batch
+    full_batches = max(1, tablet.size // spec.batch)     # timed steps use full batches only
+    buf = lgp.SampleBuffers(V, spec.batch, spec.fanouts)
+    rows = torch.empty((buf.gather_cap, D), dtype=ctx.feat_torch_dtype, device="cuda")
+    stats = torch.zeros((args.steps + args.warmup, 2), dtype=torch.int32, device="cuda")
+
+    def step(i: int):
+        b = i % full_batches
+        seeds = tablet_dev[b * spec.batch:(b + 1) * spec.batch]
+        ctx.sample_khop(seeds, spec.fanouts, spec.base_seed + i, out=buf)
+        ctx.gather_features(buf.gather_ids, n_dev=buf.n_gather, out=rows, stats=stats[i])
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ctx.check()
+    ctx.set_profiling(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.warmup, args.warmup + args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ctx.set_profiling(False)
+    prof = ctx.get_profile()
+    ctx.check()
+
+    elapsed = t1 - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    seeds_per_s = args.steps * spec.batch / elapsed
+    st = stats[args.warmup:].cpu().numpy().astype(np.int64)
+    hit_rows, miss_rows = int(st[:, 0].sum()), int(st[:, 1].sum())
+    gathered = hit_rows + miss_rows
+
+    # algorithmic bytes of one hit-gather launch: each hit row is read once and written once,
+    # plus its (row, slot) list entry
+    hit_bytes_per_row = 2 * row_bytes + 8
+    roofline = None
+    if prof.n_hit and hit_rows:
+        ach = hit_rows * hit_bytes_per_row / (prof.ms_hit * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "gather_rows_kernel (cache hits, HBM->HBM)", "achieved": round(ach, 1),
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                    "avg_launch_ms": round(prof.ms_hit / prof.n_hit, 4),
+                    "rows_per_launch": round(hit_rows / prof.n_hit, 1), "bytes_per_row": hit_bytes_per_row}
+    roofline_pcie = None
+    if prof.n_miss and miss_rows:
+        ach = miss_rows * row_bytes / (prof.ms_miss * 1e-3) / 1e9
+        roofline_pcie = {"bound": "pcie", "kernel": "gather_rows_kernel (cache misses, CPU memory->HBM)",
+                         "achieved": round(ach, 2), "peak": PCIE_PEAK_GBS, "unit": "GB/s",
+                         "frac": round(ach / PCIE_PEAK_GBS, 4), "avg_launch_ms": round(prof.ms_miss / prof.n_miss, 4),
+                         "rows_per_launch": round(miss_rows / prof.n_miss, 1), "bytes_per_row": row_bytes}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        orc = oracle.Oracle(indptr, indices, feats)
+        nb = args.cpu_batches
+        t_cpu = 0.0
+        done = 0
+        i = args.warmup
+        while True:
+            b = i % full_batches
+            seeds = tablet[b * spec.batch:(b + 1) * spec.batch]
+            c0 = time.perf_counter()
+            res = orc.sample_khop(seeds, spec.fanouts, spec.base_seed + i)
+            out = orc.gather(res.gather_ids)
+            t_cpu += time.perf_counter() - c0
+            done += 1
+            i += 1
+            del out
+            if (nb and done >= nb) or (not nb and (t_cpu > 15.0 or done >= args.steps)):
+                break
+        cpu = {"value": round(done * spec.batch / t_cpu, 1), "unit": "seeds/s", "cores": 1, "kind": "oracle",
+               "sample": f"{done} of the timed mini-batches (sample_khop + gather, same seeds and rng seeds)",
+               "ms_per_step": round(t_cpu * 1e3 / done, 2)}
+
+    line = {
+        "metric": "seeds/sec through sample+gather; feature-gather GB/s vs HBM & PCIe peak",
+        "value": round(seeds_per_s, 1), "unit": "seeds/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32 ids / opaque feature bytes", "data": "synthetic",
+        "config": {"workload": f"{spec.name}: V={V} E={E} D={D} {spec.feat_dtype} fanouts={list(spec.fanouts)} "
+                               f"batch={spec.batch} topo_cache={spec.topo_frac:g} feat_cache={spec.feat_frac:g}",
+                   "cached_topo_rows": plan.n_topo, "cached_feat_rows": plan.n_feat,
+                   "batches_in_tablet": n_batches},
+        "roofline": roofline, "roofline_pcie": roofline_pcie, "cpu_baseline": cpu,
+        "per_step": {"gather_rows": round(gathered / args.steps, 1), "hit_rate": round(hit_rows / max(gathered, 1), 4),
+                     "ms_sample": round(prof.ms_sample / max(prof.n_sample, 1), 4),
+                     "ms_partition": round(prof.ms_partition / max(prof.n_partition, 1), 4),
+                     "ms_hit_gather": round(prof.ms_hit / max(prof.n_hit, 1), 4),
+                     "ms_miss_gather": round(prof.ms_miss / max(prof.n_miss, 1), 4)},
+        "setup_s": {"generate": round(t_gen, 2), "build_hotness": round(t_hot, 3), "build_cache": round(t_cache, 3)},
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

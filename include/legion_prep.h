@@ -160,6 +160,12 @@ int lgp_sample_khop(lgp_ctx* ctx, const int32_t* seeds, int32_t n_seeds, const i
 int lgp_gather_features(lgp_ctx* ctx, const int32_t* ids, int64_t n_max, const int32_t* n_dev, void* out,
                         int32_t* stats, void* stream);
 
+/* By default lgp_gather_features runs the hit gather and then the miss gather on
+ * `stream`.  With overlap enabled the miss gather runs on a stream of the library's own
+ * beside the hit gather and `stream` waits for it: a few percent more throughput when
+ * both lists are long, at the price of the PCIe reads slowing the concurrent HBM kernel. */
+int lgp_set_overlap(lgp_ctx* ctx, int enable);
+
 /* Sticky device-side error flag (invalid vertex id met by a kernel, output overrun).
  * Synchronises `stream`, returns LGP_EDEVICE if set, and clears it. */
 int lgp_check(lgp_ctx* ctx, void* stream);

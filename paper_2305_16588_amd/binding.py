@@ -50,7 +50,7 @@ class Profile(C.Structure):
 
 EXPORTS = ["lgp_host_alloc", "lgp_host_free", "lgp_create", "lgp_destroy", "lgp_build_hotness", "lgp_get_hotness",
            "lgp_set_hotness", "lgp_plan_cache", "lgp_build_cache", "lgp_get_cache_plan", "lgp_get_cache",
-           "lgp_sample_khop", "lgp_gather_features", "lgp_check", "lgp_set_profiling", "lgp_get_profile",
+           "lgp_sample_khop", "lgp_gather_features", "lgp_set_overlap", "lgp_check", "lgp_set_profiling", "lgp_get_profile",
            "lgp_strerror", "lgp_last_error"]
 
 _lib = None
@@ -79,6 +79,7 @@ def load_library():
     L.lgp_get_cache.argtypes = [vp, vp, vp, vp, vp, vp]
     L.lgp_sample_khop.argtypes = [vp, vp, i32, vp, i32, u64, C.POINTER(_SampleOut), vp]
     L.lgp_gather_features.argtypes = [vp, vp, i64, vp, vp, vp, vp]
+    L.lgp_set_overlap.argtypes = [vp, C.c_int]
     L.lgp_check.argtypes = [vp, vp]
     L.lgp_set_profiling.argtypes = [vp, C.c_int]
     L.lgp_get_profile.argtypes = [vp, C.POINTER(Profile)]
@@ -283,6 +284,9 @@ class Context:
 
     def check(self, stream=None):
         self._ok(self._L.lgp_check(self._h, _stream_ptr(stream)))
+
+    def set_overlap(self, enable: bool):
+        self._ok(self._L.lgp_set_overlap(self._h, int(bool(enable))))
 
     def set_profiling(self, enable: bool):
         self._ok(self._L.lgp_set_profiling(self._h, int(bool(enable))))

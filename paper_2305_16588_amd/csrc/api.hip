@@ -4,6 +4,7 @@
 
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -58,6 +59,7 @@ struct lgp_ctx {
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
 
   bool profiling = false;
+  bool overlap = false;     // run the miss gather on its own stream beside the hit gather
   std::vector<EvPair> ev_used;
   std::vector<EvPair> ev_free;
 
@@ -332,6 +334,7 @@ int lgp_create(const lgp_graph* g, int device, lgp_ctx** out) {
   c->di.device = device;
   hipDeviceProp_t prop;
   if (hipGetDeviceProperties(&prop, device) == hipSuccess) c->di.num_cus = prop.multiProcessorCount;
+  if (const char* mb = std::getenv("LGP_MISS_BLOCKS")) c->di.miss_blocks = std::max(1, std::atoi(mb));
   c->g = *g;
   const void* p = nullptr;
   if ((st = device_visible(c, g->indptr, &p, "indptr")) != LGP_OK) return bail(st);
@@ -617,22 +620,28 @@ int lgp_gather_features(lgp_ctx* c, const int32_t* ids, int64_t n_max, const int
   launch_partition(c->di, ids, n_max, n_dev, c->f_remap, c->g.num_vertices, hit_row, hit_src, miss_row, miss_src,
                    counters, c->d_err, s);
   prof_end(c, ev, s);
-  // fork: misses stream in over PCIe on their own stream while hits run HBM -> HBM
-  LGP_HIP(c, hipEventRecord(c->ev_fork, s));
-  LGP_HIP(c, hipStreamWaitEvent(c->miss_stream, c->ev_fork, 0));
-  if (c->plan.n_feat < c->g.num_vertices) {
-    ev = prof_begin(c, PK_MISS, c->miss_stream);
-    launch_gather_rows(c->di, c->g.features, out, c->row_bytes, miss_row, miss_src, n_max, counters + 1, true,
-                       c->miss_stream);
-    prof_end(c, ev, c->miss_stream);
+  // Hits first (HBM -> HBM, short), then misses (PCIe, long).  With overlap enabled the
+  // misses run on a second stream beside the hits and rejoin `s` afterwards.
+  hipStream_t ms = s;
+  if (c->overlap) {
+    ms = c->miss_stream;
+    LGP_HIP(c, hipEventRecord(c->ev_fork, s));
+    LGP_HIP(c, hipStreamWaitEvent(ms, c->ev_fork, 0));
   }
   if (c->plan.n_feat > 0) {
     ev = prof_begin(c, PK_HIT, s);
     launch_gather_rows(c->di, c->fc, out, c->row_bytes, hit_row, hit_src, n_max, counters, false, s);
     prof_end(c, ev, s);
   }
-  LGP_HIP(c, hipEventRecord(c->ev_join, c->miss_stream));
-  LGP_HIP(c, hipStreamWaitEvent(s, c->ev_join, 0));
+  if (c->plan.n_feat < c->g.num_vertices) {
+    ev = prof_begin(c, PK_MISS, ms);
+    launch_gather_rows(c->di, c->g.features, out, c->row_bytes, miss_row, miss_src, n_max, counters + 1, true, ms);
+    prof_end(c, ev, ms);
+  }
+  if (c->overlap) {
+    LGP_HIP(c, hipEventRecord(c->ev_join, ms));
+    LGP_HIP(c, hipStreamWaitEvent(s, c->ev_join, 0));
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail_hip(c, e, "gather kernel launch");
   return LGP_OK;
@@ -651,6 +660,12 @@ int lgp_check(lgp_ctx* c, void* stream) {
     std::snprintf(buf, sizeof(buf), "device error flag 0x%x (1 = invalid vertex id, 2 = output overrun)", flag);
     return fail(c, LGP_EDEVICE, buf);
   }
+  return LGP_OK;
+}
+
+int lgp_set_overlap(lgp_ctx* c, int enable) {
+  if (!c) return LGP_EINVAL;
+  c->overlap = enable != 0;
   return LGP_OK;
 }
 

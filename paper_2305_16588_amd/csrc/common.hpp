@@ -24,6 +24,7 @@ constexpr int64_t kChunkBits = kChunkWords * 64;                     // 65536 ve
 struct DeviceInfo {
   int device = 0;
   int num_cus = 256;
+  int miss_blocks = 512;   // grid of the PCIe row gather
 };
 
 // Pointers every sampling kernel needs.

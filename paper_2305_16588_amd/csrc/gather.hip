@@ -21,56 +21,81 @@ __global__ void zero_counters_kernel(int32_t* counters) {
   if (threadIdx.x < 2) counters[threadIdx.x] = 0;
 }
 
+// Each wave looks up 4 x 64 consecutive ids; the workgroup reserves its share of the two
+// lists with ONE atomic per list (the two global counters are the only contended words),
+// then every lane writes its entries at wave-ballot ranks, so both lists stay in
+// ascending row order inside a workgroup.
+constexpr int kPartItems = 4;
 __global__ __launch_bounds__(256) void partition_kernel(
     const int32_t* __restrict__ ids, int64_t n_max, const int32_t* __restrict__ n_dev,
     const int32_t* __restrict__ f_remap, int64_t num_vertices, int32_t* __restrict__ hit_row,
     int32_t* __restrict__ hit_src, int32_t* __restrict__ miss_row, int32_t* __restrict__ miss_src,
     int32_t* __restrict__ counters, uint32_t* __restrict__ d_err) {
+  __shared__ int wave_hits[4], wave_miss[4], block_base[2];
   int64_t n = n_dev ? int64_t(*n_dev) : n_max;
   if (n > n_max) n = n_max;
-  const int lane = threadIdx.x & 63;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint64_t lower = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-  for (int64_t base = int64_t(blockIdx.x) * 256; base < n; base += int64_t(gridDim.x) * 256) {
-    const int64_t i = base + threadIdx.x;
-    const bool active = i < n;
-    const int32_t id = active ? ids[i] : 0;
-    const bool ok = active && uint32_t(id) < uint64_t(num_vertices);
-    if (active && !ok) atomicOr(d_err, ERR_BAD_ID);
-    const int32_t slot = ok ? f_remap[id] : -1;
-    const bool hit = ok && slot >= 0;
-    const bool miss = ok && slot < 0;
-    const uint64_t hm = __ballot(hit), mm = __ballot(miss);
-    int hbase = 0, mbase = 0;
-    if (lane == 0) {
-      if (hm) hbase = atomicAdd(&counters[0], __popcll(hm));
-      if (mm) mbase = atomicAdd(&counters[1], __popcll(mm));
+  constexpr int kTile = 256 * kPartItems;
+  for (int64_t base = int64_t(blockIdx.x) * kTile; base < n; base += int64_t(gridDim.x) * kTile) {
+    int32_t id[kPartItems], slot[kPartItems];
+    uint64_t hm[kPartItems], mm[kPartItems];
+    int nh = 0, nm = 0;
+#pragma unroll
+    for (int j = 0; j < kPartItems; ++j) {
+      const int64_t i = base + wave * (64 * kPartItems) + j * 64 + lane;
+      const bool active = i < n;
+      id[j] = active ? ids[i] : 0;
+      const bool ok = active && uint32_t(id[j]) < uint64_t(num_vertices);
+      if (active && !ok) atomicOr(d_err, ERR_BAD_ID);
+      slot[j] = ok ? f_remap[id[j]] : -1;
+      hm[j] = __ballot(ok && slot[j] >= 0);
+      mm[j] = __ballot(ok && slot[j] < 0);
+      nh += __popcll(hm[j]);
+      nm += __popcll(mm[j]);
     }
-    hbase = __shfl(hbase, 0, 64);
-    mbase = __shfl(mbase, 0, 64);
-    if (hit) {
-      const int pos = hbase + __popcll(hm & lower);
-      hit_row[pos] = int32_t(i);
-      hit_src[pos] = slot;
-    } else if (miss) {
-      const int pos = mbase + __popcll(mm & lower);
-      miss_row[pos] = int32_t(i);
-      miss_src[pos] = id;
+    if (lane == 0) { wave_hits[wave] = nh; wave_miss[wave] = nm; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      const int th = wave_hits[0] + wave_hits[1] + wave_hits[2] + wave_hits[3];
+      const int tm = wave_miss[0] + wave_miss[1] + wave_miss[2] + wave_miss[3];
+      block_base[0] = th ? atomicAdd(&counters[0], th) : 0;
+      block_base[1] = tm ? atomicAdd(&counters[1], tm) : 0;
     }
+    __syncthreads();
+    int hpos = block_base[0], mpos = block_base[1];
+    for (int w = 0; w < wave; ++w) { hpos += wave_hits[w]; mpos += wave_miss[w]; }
+#pragma unroll
+    for (int j = 0; j < kPartItems; ++j) {
+      const int64_t i = base + wave * (64 * kPartItems) + j * 64 + lane;
+      const uint64_t bit = 1ull << lane;
+      if (hm[j] & bit) {
+        const int pos = hpos + __popcll(hm[j] & lower);
+        hit_row[pos] = int32_t(i);
+        hit_src[pos] = slot[j];
+      } else if (mm[j] & bit) {
+        const int pos = mpos + __popcll(mm[j] & lower);
+        miss_row[pos] = int32_t(i);
+        miss_src[pos] = id[j];
+      }
+      hpos += __popcll(hm[j]);
+      mpos += __popcll(mm[j]);
+    }
+    __syncthreads();                               // LDS is reused by the next tile
   }
 }
 
-template <typename VecT, bool STREAMING>
-__device__ __forceinline__ VecT load_chunk(const VecT* p) {
-  if (STREAMING) return __builtin_nontemporal_load(p);
-  return *p;
-}
-
-template <typename VecT, int UNROLL, bool STREAMING>
-__global__ __launch_bounds__(256) void gather_rows_kernel(const VecT* __restrict__ src, VecT* __restrict__ dst,
-                                                          uint32_t cpr, uint64_t inv_cpr,
-                                                          const int32_t* __restrict__ row,
-                                                          const int32_t* __restrict__ srcrow, int64_t n_max,
-                                                          const int32_t* __restrict__ n_dev) {
+// ---- cache hits: HBM -> HBM ------------------------------------------------
+// A wavefront takes 64 list entries and walks their rows as one flat run of chunks:
+// all 64 lanes stay busy for any row width and UNROLL loads per lane are in flight
+// before the first store.  Output rows are written once and not read again by this
+// path, so they are stored non-temporally.
+template <typename VecT, int UNROLL>
+__global__ __launch_bounds__(256) void gather_rows_flat_kernel(const VecT* __restrict__ src, VecT* __restrict__ dst,
+                                                               uint32_t cpr, uint64_t inv_cpr,
+                                                               const int32_t* __restrict__ row,
+                                                               const int32_t* __restrict__ srcrow, int64_t n_max,
+                                                               const int32_t* __restrict__ n_dev) {
   int64_t n = n_dev ? int64_t(*n_dev) : n_max;
   if (n > n_max) n = n_max;
   const int lane = threadIdx.x & 63;
@@ -95,30 +120,88 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const VecT* __restrict
         const int32_t r = __shfl(my_row, int(k), 64);
         const int32_t sr = __shfl(my_src, int(k), 64);
         doff[u] = int64_t(r) * cpr + col;
-        if (ok[u]) val[u] = load_chunk<VecT, STREAMING>(src + (int64_t(sr) * cpr + col));
+        if (ok[u]) val[u] = src[int64_t(sr) * cpr + col];
       }
 #pragma unroll
       for (int u = 0; u < UNROLL; ++u)
-        if (ok[u]) dst[doff[u]] = val[u];
+        if (ok[u]) __builtin_nontemporal_store(val[u], dst + doff[u]);
     }
   }
 }
 
-template <typename VecT, int UNROLL>
-void launch_rows(const DeviceInfo& di, const void* src, void* dst, int64_t row_bytes, const int32_t* row,
-                 const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, bool streaming, hipStream_t s) {
+// ---- cache misses and cache fill: CPU memory -> HBM over PCIe ---------------
+// Reads of CPU memory are not cached on the GPU and travel as whole 128-byte lines, so
+// a line requested by two different load instructions crosses the link twice.  Here a
+// group of G >= chunks-per-row lanes owns a whole row, so one instruction requests each
+// line of the row exactly once; UNROLL rows per group are in flight before the first
+// store.  Rows wider than 64 chunks are walked in 64-chunk pieces.
+template <typename VecT, int G, int UNROLL>
+__global__ __launch_bounds__(256) void gather_rows_group_kernel(const VecT* __restrict__ src, VecT* __restrict__ dst,
+                                                                uint32_t cpr, const int32_t* __restrict__ row,
+                                                                const int32_t* __restrict__ srcrow, int64_t n_max,
+                                                                const int32_t* __restrict__ n_dev) {
+  int64_t n = n_dev ? int64_t(*n_dev) : n_max;
+  if (n > n_max) n = n_max;
+  const uint32_t sub = threadIdx.x % G;
+  const int64_t group = (int64_t(blockIdx.x) * 256 + threadIdx.x) / G;
+  const int64_t n_groups = int64_t(gridDim.x) * (256 / G);
+  for (int64_t e0 = group * UNROLL; e0 < n; e0 += n_groups * UNROLL) {
+    int64_t so[UNROLL], dof[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int64_t e = e0 + u;
+      const bool ok = e < n;
+      so[u] = ok ? int64_t(srcrow[e]) * cpr : -1;
+      dof[u] = ok ? int64_t(row ? row[e] : int32_t(e)) * cpr : 0;
+    }
+    for (uint32_t c0 = 0; c0 < cpr; c0 += G) {
+      const uint32_t col = c0 + sub;
+      VecT val[UNROLL];
+#pragma unroll
+      for (int u = 0; u < UNROLL; ++u)
+        if (so[u] >= 0 && col < cpr) val[u] = __builtin_nontemporal_load(src + so[u] + col);
+#pragma unroll
+      for (int u = 0; u < UNROLL; ++u)
+        if (so[u] >= 0 && col < cpr) dst[dof[u] + col] = val[u];
+    }
+  }
+}
+
+inline unsigned blocks_for(int64_t work_blocks, int64_t limit) {
+  int64_t b = work_blocks < limit ? work_blocks : limit;
+  return unsigned(b < 1 ? 1 : b);
+}
+
+template <typename VecT>
+void launch_flat(const DeviceInfo& di, const void* src, void* dst, int64_t row_bytes, const int32_t* row,
+                 const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, hipStream_t s) {
   const uint32_t cpr = uint32_t(row_bytes / int64_t(sizeof(VecT)));
   const uint64_t inv = (uint64_t(1) << 32) / cpr + 1;          // exact for flat < 64 * cpr, cpr <= 4096
-  int64_t blocks = (n_max + 255) / 256;                        // one wave per 64 rows
-  const int64_t full = int64_t(di.num_cus) * 8;
-  if (blocks > full) blocks = full;
-  if (blocks < 1) blocks = 1;
-  if (streaming)
-    hipLaunchKernelGGL((gather_rows_kernel<VecT, UNROLL, true>), dim3(unsigned(blocks)), dim3(256), 0, s,
-                       static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, inv, row, srcrow, n_max, n_dev);
-  else
-    hipLaunchKernelGGL((gather_rows_kernel<VecT, UNROLL, false>), dim3(unsigned(blocks)), dim3(256), 0, s,
-                       static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, inv, row, srcrow, n_max, n_dev);
+  const unsigned blocks = blocks_for((n_max + 255) / 256, int64_t(di.num_cus) * 8);
+  hipLaunchKernelGGL((gather_rows_flat_kernel<VecT, 4>), dim3(blocks), dim3(256), 0, s,
+                     static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, inv, row, srcrow, n_max, n_dev);
+}
+
+template <typename VecT, int G>
+void launch_group_g(const DeviceInfo& di, const void* src, void* dst, uint32_t cpr, const int32_t* row,
+                    const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, hipStream_t s) {
+  constexpr int U = 4;
+  // PCIe needs far fewer waves than HBM to stay saturated; a small grid leaves the CUs
+  // to the hit gather that runs beside it.
+  const unsigned blocks = blocks_for((n_max + (256 / G) * U - 1) / ((256 / G) * U), int64_t(di.miss_blocks));
+  hipLaunchKernelGGL((gather_rows_group_kernel<VecT, G, U>), dim3(blocks), dim3(256), 0, s,
+                     static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, row, srcrow, n_max, n_dev);
+}
+
+template <typename VecT>
+void launch_group(const DeviceInfo& di, const void* src, void* dst, int64_t row_bytes, const int32_t* row,
+                  const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, hipStream_t s) {
+  const uint32_t cpr = uint32_t(row_bytes / int64_t(sizeof(VecT)));
+  if (cpr <= 4) launch_group_g<VecT, 4>(di, src, dst, cpr, row, srcrow, n_max, n_dev, s);
+  else if (cpr <= 8) launch_group_g<VecT, 8>(di, src, dst, cpr, row, srcrow, n_max, n_dev, s);
+  else if (cpr <= 16) launch_group_g<VecT, 16>(di, src, dst, cpr, row, srcrow, n_max, n_dev, s);
+  else if (cpr <= 32) launch_group_g<VecT, 32>(di, src, dst, cpr, row, srcrow, n_max, n_dev, s);
+  else launch_group_g<VecT, 64>(di, src, dst, cpr, row, srcrow, n_max, n_dev, s);
 }
 
 __global__ void copy_i32_kernel(const int32_t* src, int32_t* dst, int n) {
@@ -131,7 +214,7 @@ void launch_partition(const DeviceInfo& di, const int32_t* ids, int64_t n_max, c
                       const int32_t* f_remap, int64_t num_vertices, int32_t* hit_row, int32_t* hit_src,
                       int32_t* miss_row, int32_t* miss_src, int32_t* counters, uint32_t* d_err, hipStream_t s) {
   hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(64), 0, s, counters);
-  int64_t blocks = (n_max + 255) / 256;
+  int64_t blocks = (n_max + 256 * kPartItems - 1) / (256 * kPartItems);
   const int64_t full = int64_t(di.num_cus) * 8;
   if (blocks > full) blocks = full;
   if (blocks < 1) blocks = 1;
@@ -143,14 +226,16 @@ void launch_gather_rows(const DeviceInfo& di, const void* src, void* dst, int64_
                         const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, bool streaming, hipStream_t s) {
   if (n_max <= 0) return;
   const uintptr_t align = uintptr_t(src) | uintptr_t(dst) | uintptr_t(row_bytes);
-  if ((align & 15u) == 0)
-    launch_rows<u32x4, 4>(di, src, dst, row_bytes, row, srcrow, n_max, n_dev, streaming, s);
-  else if ((align & 7u) == 0)
-    launch_rows<u32x2, 4>(di, src, dst, row_bytes, row, srcrow, n_max, n_dev, streaming, s);
-  else if ((align & 3u) == 0)
-    launch_rows<uint32_t, 4>(di, src, dst, row_bytes, row, srcrow, n_max, n_dev, streaming, s);
-  else
-    launch_rows<uint16_t, 4>(di, src, dst, row_bytes, row, srcrow, n_max, n_dev, streaming, s);
+#define LGP_ROWS(VecT)                                                                        \
+  do {                                                                                        \
+    if (streaming) launch_group<VecT>(di, src, dst, row_bytes, row, srcrow, n_max, n_dev, s); \
+    else launch_flat<VecT>(di, src, dst, row_bytes, row, srcrow, n_max, n_dev, s);            \
+  } while (0)
+  if ((align & 15u) == 0) LGP_ROWS(u32x4);
+  else if ((align & 7u) == 0) LGP_ROWS(u32x2);
+  else if ((align & 3u) == 0) LGP_ROWS(uint32_t);
+  else LGP_ROWS(uint16_t);
+#undef LGP_ROWS
 }
 
 void launch_copy_i32(const int32_t* src, int32_t* dst, int n, hipStream_t s) {
