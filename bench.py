@@ -26,6 +26,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 PCIE_PEAK_GBS = 63.0           # PCIe Gen5 x16, one direction: 32 GT/s * 16 * 128/130 / 8
+# HBM bytes per hit row measured with rocprofv3 --pmc (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors a plain
+# 1 GiB copy gives; see profiles/bench_mid_workload.md), keyed by row width in bytes.
+MEASURED_HBM_BYTES_PER_HIT_ROW = {400: 911.0}
 
 
 def main() -> int:
@@ -37,6 +40,9 @@ def main() -> int:
     ap.add_argument("--feat-frac", type=float, default=None, help="override the feature-cache ratio")
     ap.add_argument("--topo-frac", type=float, default=None, help="override the topology-cache ratio")
     ap.add_argument("--overlap", action="store_true", help="miss gather on a second stream beside the hit gather")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batches", type=int, default=0, help="oracle batches to time (0 = pick for ~15 s)")
     args = ap.parse_args()
@@ -105,6 +111,12 @@ def main() -> int:
         step(i)
     torch.cuda.synchronize()
     ctx.check()
+    if args.copy_calibration:
+        a = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")      # 1 GiB
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
     ctx.set_profiling(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -130,7 +142,9 @@ def main() -> int:
     if prof.n_hit and hit_rows:
         ach = hit_rows * hit_bytes_per_row / (prof.ms_hit * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": "gather_rows_kernel (cache hits, HBM->HBM)", "achieved": round(ach, 1),
-                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
+                    "traffic": (round(MEASURED_HBM_BYTES_PER_HIT_ROW[row_bytes] * hit_rows / prof.n_hit)
+                                if row_bytes in MEASURED_HBM_BYTES_PER_HIT_ROW else None),
                     "avg_launch_ms": round(prof.ms_hit / prof.n_hit, 4),
                     "rows_per_launch": round(hit_rows / prof.n_hit, 1), "bytes_per_row": hit_bytes_per_row}
     roofline_pcie = None
