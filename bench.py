@@ -43,6 +43,8 @@ def main() -> int:
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
+    ap.add_argument("--features-on-device", action="store_true",
+                    help="keep the source feature table in HBM (for tables beyond the box's 64 GiB pinned-memory limit)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batches", type=int, default=0, help="oracle batches to time (0 = pick for ~15 s)")
     args = ap.parse_args()
@@ -72,17 +74,27 @@ def main() -> int:
         spec = replace(spec, topo_frac=args.topo_frac)
 
     t0 = time.time()
-    indptr, indices = datagen.make_graph(spec, device="cuda", indices_alloc=lambda n: lgp.pinned_empty(n, np.int32))
-    indptr = lgp.pinned_copy(indptr)
+    indptr = lgp.pinned_empty(spec.num_vertices + 1, np.int64 if spec.index64 else np.int32)
+    _, indices = datagen.make_graph(spec, device="cuda", indptr_out=indptr,
+                                    indices_alloc=lambda n: lgp.pinned_empty(n, np.int32))
     npdt = np.float32 if spec.feat_dtype == "float32" else np.float16
-    feats = lgp.pinned_empty((spec.num_vertices, spec.feat_dim), npdt)
+    if args.features_on_device:
+        feats = np.empty((spec.num_vertices, spec.feat_dim), npdt)
+    else:
+        feats = lgp.pinned_empty((spec.num_vertices, spec.feat_dim), npdt)
     datagen.make_features(spec, device="cuda", out=feats)
+    feats_src = feats
+    if args.features_on_device:
+        feats_src = torch.empty(feats.shape, device="cuda",
+                                dtype=torch.float32 if spec.feat_dtype == "float32" else torch.float16)
+        for lo in range(0, spec.num_vertices, 1 << 22):
+            feats_src[lo:lo + (1 << 22)].copy_(torch.from_numpy(feats[lo:lo + (1 << 22)]))
     tablet = datagen.make_tablet(spec)
     t_gen = time.time() - t0
     V, E, D = spec.num_vertices, int(indices.size), spec.feat_dim
     row_bytes = D * feats.dtype.itemsize
 
-    ctx = lgp.Context(indptr, indices, feats)
+    ctx = lgp.Context(indptr, indices, feats_src)
     ctx.set_overlap(args.overlap)
     tablet_dev = torch.from_numpy(tablet).cuda()
     torch.cuda.synchronize()
@@ -185,7 +197,8 @@ def main() -> int:
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32 ids / opaque feature bytes", "data": "synthetic",
         "config": {"workload": f"{spec.name}: V={V} E={E} D={D} {spec.feat_dtype} fanouts={list(spec.fanouts)} "
-                               f"batch={spec.batch} topo_cache={spec.topo_frac:g} feat_cache={spec.feat_frac:g}",
+                               f"batch={spec.batch} topo_cache={spec.topo_frac:g} feat_cache={spec.feat_frac:g}"
+                               + (" (source feature table in HBM)" if args.features_on_device else ""),
                    "cached_topo_rows": plan.n_topo, "cached_feat_rows": plan.n_feat,
                    "batches_in_tablet": n_batches},
         "roofline": roofline, "roofline_pcie": roofline_pcie, "cpu_baseline": cpu,

@@ -103,7 +103,9 @@ def make_graph(spec: WorkloadSpec, device: str = "cpu", isolated: float = 0.001,
 
     Returns (indptr, indices) as numpy arrays: indptr int64 if spec.index64 else
     int32 (V + 1 entries), indices int32.  `indices_alloc(n)` may supply the
-    destination array for the n column ids (e.g. pinned host memory).
+    destination array (e.g. pinned host memory); it is asked for room for all
+    draws and `indices` is the prefix the simple graph fills.  `indptr_out`
+    (V + 1 entries of the right dtype) likewise receives the offsets.
     """
     V, E = spec.num_vertices, spec.num_edges
     dev = torch.device(device)
@@ -148,7 +150,10 @@ def make_graph(spec: WorkloadSpec, device: str = "cpu", isolated: float = 0.001,
         nxt = int(torch.searchsorted(csum, torch.tensor(base + chunk_edges, device=dev), right=True).item())
         bounds.append(min(V, max(nxt, bounds[-1] + 1)))
     final_deg = torch.zeros(V, dtype=torch.int64, device=dev)
-    pieces = []
+    # destination sized for the draws; the simple graph uses a prefix of it
+    indices_full = indices_alloc(total_draws) if indices_alloc is not None else np.empty(total_draws, dtype=np.int32)
+    dst_t = torch.from_numpy(indices_full) if total_draws else None
+    at = 0
     for lo, hi in zip(bounds[:-1], bounds[1:]):
         d = deg[lo:hi]
         n = int(d.sum().item())
@@ -157,30 +162,30 @@ def make_graph(spec: WorkloadSpec, device: str = "cpu", isolated: float = 0.001,
         src = torch.repeat_interleave(torch.arange(lo, hi, device=dev, dtype=torch.int64), d)
         u = torch.rand(n, generator=gen, device=dev, dtype=torch.float64)
         rank = inv_cdf(u).floor().to(torch.int64).clamp_(0, V - 1)
+        del u
         dst = perm_dst[rank]
+        del rank
         keep = dst != src
         key = (src[keep] << 32) | dst[keep]
+        del src, dst, keep
         key = torch.unique(key)                               # sorted: by row, then by column id
-        rows = key >> 32
-        final_deg[lo:hi] = torch.bincount(rows - lo, minlength=hi - lo)
-        pieces.append((key & 0xFFFFFFFF).to(torch.int32).cpu())
-        del src, u, rank, dst, keep, key, rows
+        final_deg[lo:hi] = torch.bincount((key >> 32) - lo, minlength=hi - lo)
+        cols = (key & 0xFFFFFFFF).to(torch.int32)
+        dst_t[at:at + cols.numel()].copy_(cols)
+        at += cols.numel()
+        del key, cols
     n_edges = int(final_deg.sum().item())
-    indices = indices_alloc(n_edges) if indices_alloc is not None else np.empty(n_edges, dtype=np.int32)
-    at = 0
-    for p in pieces:
-        indices[at:at + p.numel()] = p.numpy()
-        at += p.numel()
     assert at == n_edges
+    indices = indices_full[:n_edges]
     idt = torch.int64 if spec.index64 else torch.int32
     assert spec.index64 or n_edges < 2 ** 31
     indptr_t = torch.zeros(V + 1, dtype=torch.int64, device=dev)
     indptr_t[1:] = torch.cumsum(final_deg, 0)
-    indptr_np = indptr_t.to(idt).cpu().numpy()
     if indptr_out is not None:
-        indptr_out[:] = indptr_np
+        torch.from_numpy(indptr_out).copy_(indptr_t.to(idt))
         indptr_np = indptr_out
-    del total_draws
+    else:
+        indptr_np = indptr_t.to(idt).cpu().numpy()
     return indptr_np, indices
 
 
@@ -197,7 +202,7 @@ def make_features(spec: WorkloadSpec, device: str = "cpu", out: np.ndarray | Non
     for lo in range(0, V, chunk_rows):
         hi = min(V, lo + chunk_rows)
         x = torch.randn(hi - lo, D, generator=gen, device=dev, dtype=torch.float32).to(tdt)
-        out[lo:hi] = x.cpu().numpy()
+        torch.from_numpy(out[lo:hi]).copy_(x)
     return out
 
 

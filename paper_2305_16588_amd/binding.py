@@ -249,15 +249,17 @@ class Context:
         self._ok(self._L.lgp_get_cache_plan(self._h, C.byref(p)))
         return p
 
-    def get_cache(self):
+    def get_cache(self, contents: bool = True):
+        """(topo_ids, t_indptr, t_indices, feat_ids, feat_rows); the two content arrays are None if not asked for."""
         p = self.get_cache_plan()
         topo_ids = np.empty(p.n_topo, dtype=np.int32)
         t_indptr = np.empty(p.n_topo + 1, dtype=np.int64)
-        t_indices = np.empty(p.topo_edges, dtype=np.int32)
         feat_ids = np.empty(p.n_feat, dtype=np.int32)
-        feat_rows = np.empty((p.n_feat, self.feat_dim * self.elem_bytes), dtype=np.uint8)
-        self._ok(self._L.lgp_get_cache(self._h, topo_ids.ctypes.data, t_indptr.ctypes.data, t_indices.ctypes.data,
-                                       feat_ids.ctypes.data, feat_rows.ctypes.data))
+        t_indices = np.empty(p.topo_edges, dtype=np.int32) if contents else None
+        feat_rows = np.empty((p.n_feat, self.feat_dim * self.elem_bytes), dtype=np.uint8) if contents else None
+        self._ok(self._L.lgp_get_cache(self._h, topo_ids.ctypes.data, t_indptr.ctypes.data,
+                                       t_indices.ctypes.data if contents else None, feat_ids.ctypes.data,
+                                       feat_rows.ctypes.data if contents else None))
         return topo_ids, t_indptr, t_indices, feat_ids, feat_rows
 
     def sample_khop(self, seeds: torch.Tensor, fanouts, rng_seed: int, out: SampleBuffers | None = None,

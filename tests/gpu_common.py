@@ -10,24 +10,37 @@ import paper_2305_16588_amd as lgp
 
 
 class Workload:
-    def __init__(self, spec, device_gen: str = "cpu", with_features: bool = True, indptr_dtype=None):
+    def __init__(self, spec, device_gen: str = "cpu", with_features: bool = True, features_on_device: bool = False):
+        """features_on_device: keep the source feature table in HBM instead of pinned CPU memory (the
+        library accepts a device pointer in its place).  Used when the table does not fit under the box's
+        pinned-memory limit; the oracle still reads a host copy of the same bytes."""
         self.spec = spec
-        indptr, indices = datagen.make_graph(spec, device=device_gen)
-        if indptr_dtype is not None:
-            indptr = indptr.astype(indptr_dtype)
-        self.indptr = lgp.pinned_copy(indptr)
-        self.indices = lgp.pinned_copy(indices)
+        idt = np.int64 if spec.index64 else np.int32
+        self.indptr = lgp.pinned_empty(spec.num_vertices + 1, idt)
+        _, self.indices = datagen.make_graph(spec, device=device_gen, indptr_out=self.indptr,
+                                             indices_alloc=lambda n: lgp.pinned_empty(n, np.int32))
         self.features = None
         if with_features:
             npdt = np.float32 if spec.feat_dtype == "float32" else np.float16
-            self.features = lgp.pinned_empty((spec.num_vertices, spec.feat_dim), npdt)
+            if features_on_device:
+                self.features = np.empty((spec.num_vertices, spec.feat_dim), npdt)
+            else:
+                self.features = lgp.pinned_empty((spec.num_vertices, spec.feat_dim), npdt)
             datagen.make_features(spec, device=device_gen, out=self.features)
         self.tablet = datagen.make_tablet(spec)
         self.tablet_dev = torch.from_numpy(self.tablet).cuda()
-        self.ctx = lgp.Context(self.indptr, self.indices, self.features)
+        self.features_dev = None
+        if with_features and features_on_device:
+            self.features_dev = torch.empty((spec.num_vertices, spec.feat_dim), device="cuda",
+                                            dtype=torch.float32 if spec.feat_dtype == "float32" else torch.float16)
+            step = 1 << 22
+            for lo in range(0, spec.num_vertices, step):
+                self.features_dev[lo:lo + step].copy_(torch.from_numpy(self.features[lo:lo + step]))
+        self.ctx = lgp.Context(self.indptr, self.indices,
+                               self.features_dev if self.features_dev is not None else self.features)
         self.orc = oracle.Oracle(self.indptr, self.indices, self.features)
         self.V = spec.num_vertices
-        self.E = int(indices.size)
+        self.E = int(self.indices.size)
 
     def batch(self, b: int):
         lo = b * self.spec.batch
