@@ -98,7 +98,7 @@ int lgp_host_free(void* ptr);
 
 /* Create a context for `g` on GPU `device`.  Validates sizes and pointer kinds
  * (LGP_EINVAL if an array is not GPU-addressable), allocates two empty remap
- * tables, two hotness vectors and two dedup byte maps (about 18 bytes per vertex)
+ * tables, two hotness vectors and the dedup bitmaps (about 16.3 bytes per vertex)
  * and starts with empty caches, so sampling and gathering already work, entirely
  * from CPU memory (the "topology in CPU memory" mode of Sec. 3.2).  Synchronous. */
 int lgp_create(const lgp_graph* g, int device, lgp_ctx** out);

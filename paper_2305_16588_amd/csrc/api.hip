@@ -25,15 +25,15 @@ struct lgp_ctx {
   DeviceInfo di;
   lgp_graph g{};           // pointers already translated to device-visible addresses
   int64_t row_bytes = 0;
-  int64_t n_chunks = 0;    // dedup byte-map chunks
+  int64_t n_chunks = 0;    // dedup bitmap chunks
 
   int32_t* t_remap = nullptr;
   int32_t* f_remap = nullptr;
   uint32_t* topo_hot = nullptr;
   uint32_t* feat_hot = nullptr;
   bool have_hot = false;
-  uint8_t* fmap = nullptr;     // frontier dedup byte map (one flag per vertex)
-  uint8_t* gmap = nullptr;     // gather-set dedup byte map
+  uint64_t* fbits = nullptr;   // frontier dedup bitmap
+  uint64_t* gbits = nullptr;   // gather-set dedup bitmap
   int32_t* chunk_counts = nullptr;
   uint32_t* d_err = nullptr;
   int32_t* counters = nullptr;  // {n_hit, n_miss}
@@ -192,32 +192,34 @@ int sample_core(lgp_ctx* c, const int32_t* seeds, int32_t n_seeds, const int32_t
                 uint64_t rng_seed, const lgp_sample_out* out, hipStream_t s) {
   const bool hot_mode = (out == nullptr);
   const int64_t V = c->g.num_vertices;
+  uint32_t* fbits32 = reinterpret_cast<uint32_t*>(c->fbits);
+  uint32_t* gbits32 = reinterpret_cast<uint32_t*>(c->gbits);
   int32_t* n_frontier = hot_mode ? c->hs_n : out->n_frontier;
   const TopoView tv = topo_view(c, !hot_mode);
 
-  launch_mark_ids(c->di, seeds, n_seeds, V, c->gmap, n_frontier, c->d_err, s);
+  launch_mark_ids(c->di, seeds, n_seeds, V, gbits32, n_frontier, c->d_err, s);
   const int32_t* frontier = seeds;
   int64_t cap = n_seeds;
   for (int h = 0; h < n_hops; ++h) {
     const bool last = (h + 1 == n_hops);
     // the last hop's samples only feed the gather set, so they are marked there directly
     launch_sample_hop(c->di, tv, frontier, n_frontier + h, cap, fanouts[h], h, rng_seed,
-                      hot_mode ? nullptr : out->nbr[h], hot_mode ? nullptr : out->cnt[h], last ? c->gmap : c->fmap,
+                      hot_mode ? nullptr : out->nbr[h], hot_mode ? nullptr : out->cnt[h], last ? gbits32 : fbits32,
                       hot_mode ? c->topo_hot : nullptr, c->d_err, s);
     if (!last) {
       int32_t* next = hot_mode ? c->hs_frontier[h + 1] : out->frontier[h + 1];
       const int64_t next_cap = hot_mode ? c->hs_cap[h + 1] : out->cap[h + 1];
-      launch_compact(c->di, c->fmap, c->gmap, c->n_chunks, c->chunk_counts, next, next_cap, n_frontier + h + 1,
+      launch_compact(c->di, c->fbits, c->gbits, c->n_chunks, c->chunk_counts, next, next_cap, n_frontier + h + 1,
                      nullptr, c->d_err, s);
       frontier = next;
       cap = next_cap;
     }
   }
   if (hot_mode)
-    launch_compact(c->di, c->gmap, nullptr, c->n_chunks, c->chunk_counts, nullptr, 0, nullptr, c->feat_hot, c->d_err,
+    launch_compact(c->di, c->gbits, nullptr, c->n_chunks, c->chunk_counts, nullptr, 0, nullptr, c->feat_hot, c->d_err,
                    s);
   else
-    launch_compact(c->di, c->gmap, nullptr, c->n_chunks, c->chunk_counts, out->gather_ids, out->gather_cap,
+    launch_compact(c->di, c->gbits, nullptr, c->n_chunks, c->chunk_counts, out->gather_ids, out->gather_cap,
                    out->n_gather, nullptr, c->d_err, s);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail_hip(c, e, "sampling kernel launch");
@@ -351,8 +353,8 @@ int lgp_create(const lgp_graph* g, int device, lgp_ctx** out) {
     if (vec == 0 || c->row_bytes / vec > 4096) return bail(LGP_EUNSUPPORTED);
   }
   const int64_t V = g->num_vertices;
-  c->n_chunks = (V + kChunkIds - 1) / kChunkIds;
-  const size_t map_bytes = size_t(c->n_chunks) * size_t(kChunkIds);
+  c->n_chunks = (V + kChunkBits - 1) / kChunkBits;
+  const size_t words = size_t(c->n_chunks) * size_t(kChunkWords);
   hipError_t e = hipSuccess;
   auto step = [&](hipError_t r) {
     if (e == hipSuccess) e = r;
@@ -361,8 +363,8 @@ int lgp_create(const lgp_graph* g, int device, lgp_ctx** out) {
   step(dev_alloc(&c->f_remap, size_t(V)));
   step(dev_alloc(&c->topo_hot, size_t(V)));
   step(dev_alloc(&c->feat_hot, size_t(V)));
-  step(dev_alloc(&c->fmap, map_bytes));
-  step(dev_alloc(&c->gmap, map_bytes));
+  step(dev_alloc(&c->fbits, words));
+  step(dev_alloc(&c->gbits, words));
   step(dev_alloc(&c->chunk_counts, size_t(c->n_chunks)));
   step(dev_alloc(&c->d_err, 1));
   step(dev_alloc(&c->counters, 2));
@@ -371,8 +373,8 @@ int lgp_create(const lgp_graph* g, int device, lgp_ctx** out) {
   if (e == hipSuccess) e = hipMemset(c->f_remap, 0xff, sizeof(int32_t) * size_t(V));
   if (e == hipSuccess) e = hipMemset(c->topo_hot, 0, sizeof(uint32_t) * size_t(V));
   if (e == hipSuccess) e = hipMemset(c->feat_hot, 0, sizeof(uint32_t) * size_t(V));
-  if (e == hipSuccess) e = hipMemset(c->fmap, 0, map_bytes);
-  if (e == hipSuccess) e = hipMemset(c->gmap, 0, map_bytes);
+  if (e == hipSuccess) e = hipMemset(c->fbits, 0, sizeof(uint64_t) * words);
+  if (e == hipSuccess) e = hipMemset(c->gbits, 0, sizeof(uint64_t) * words);
   if (e == hipSuccess) e = hipMemset(c->d_err, 0, sizeof(uint32_t));
   if (e == hipSuccess) e = hipMemset(c->counters, 0, 2 * sizeof(int32_t));
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->miss_stream, hipStreamNonBlocking);
@@ -392,7 +394,7 @@ int lgp_destroy(lgp_ctx* c) {
   (void)hipSetDevice(c->di.device);
   (void)hipDeviceSynchronize();
   free_cache(c);
-  void* ptrs[] = {c->t_remap, c->f_remap, c->topo_hot, c->feat_hot, c->fmap, c->gmap, c->chunk_counts,
+  void* ptrs[] = {c->t_remap, c->f_remap, c->topo_hot, c->feat_hot, c->fbits, c->gbits, c->chunk_counts,
                   c->d_err,   c->counters, c->order_t, c->order_f,  c->lists, c->hs_n};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);

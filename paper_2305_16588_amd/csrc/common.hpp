@@ -15,10 +15,11 @@ namespace lgp {
 // Device-side error bits (sticky, OR-ed into ctx->d_err).
 enum : uint32_t { ERR_BAD_ID = 1u, ERR_OVERRUN = 2u };
 
-// One chunk of a dedup byte map (one byte per vertex) = what one workgroup of the
-// compaction kernels covers.
+// One dedup bitmap chunk = what one workgroup of the compaction kernels covers.
 constexpr int kCompactThreads = 256;
-constexpr int64_t kChunkIds = 65536;
+constexpr int kWordsPerThread = 4;                                   // 64-bit words
+constexpr int64_t kChunkWords = int64_t(kCompactThreads) * kWordsPerThread;
+constexpr int64_t kChunkBits = kChunkWords * 64;                     // 65536 vertices per workgroup
 
 struct DeviceInfo {
   int device = 0;
@@ -39,21 +40,21 @@ struct TopoView {
 
 // ---- sampler.hip ----------------------------------------------------------
 // Expand frontier[0 .. *n_frontier) with fan-out f at hop `hop`.  Writes nbr / cnt
-// (either may be null), stores 1 to mark[u] for every sampled neighbour u,
+// (either may be null), sets the bit of every sampled neighbour in `mark_bits`,
 // adds cnt to topo_hot[v] if topo_hot is given.
 void launch_sample_hop(const DeviceInfo& di, const TopoView& tv, const int32_t* frontier, const int32_t* n_frontier,
                        int64_t cap, int32_t fanout, int32_t hop, uint64_t rng_seed, int32_t* nbr, int32_t* cnt,
-                       uint8_t* mark, uint32_t* topo_hot, uint32_t* d_err, hipStream_t s);
-// mark[id] = 1 for every id in ids[0 .. n); store n to *n_out (if given).
-void launch_mark_ids(const DeviceInfo& di, const int32_t* ids, int32_t n, int64_t num_vertices, uint8_t* mark,
+                       uint32_t* mark_bits, uint32_t* topo_hot, uint32_t* d_err, hipStream_t s);
+// Set the bit of every id in ids[0 .. n) and store n to *n_out (if given).
+void launch_mark_ids(const DeviceInfo& di, const int32_t* ids, int32_t n, int64_t num_vertices, uint32_t* bits,
                      int32_t* n_out, uint32_t* d_err, hipStream_t s);
 
 // ---- compact.hip ----------------------------------------------------------
-// Turn the byte map `map` (n_chunks * kChunkIds flags, each 0 or 1) into the ascending id
-// list out[0 .. *n_out).  If or_into is given, marks are OR-ed into that map; `map` is
-// cleared.  If bump is given, bump[id] += 1 for every mark.  With n_out == nullptr no
+// Turn the bitmap `bits` (n_chunks * kChunkWords 64-bit words) into the ascending id
+// list out[0 .. *n_out).  If or_into is given, bits are OR-ed into it; `bits` is
+// cleared.  If bump is given, bump[id] += 1 for every set bit.  With n_out == nullptr no
 // list is produced: only the OR / clear / bump side effects happen.
-void launch_compact(const DeviceInfo& di, uint8_t* map, uint8_t* or_into, int64_t n_chunks, int32_t* chunk_counts,
+void launch_compact(const DeviceInfo& di, uint64_t* bits, uint64_t* or_into, int64_t n_chunks, int32_t* chunk_counts,
                     int32_t* out, int64_t out_cap, int32_t* n_out, uint32_t* bump, uint32_t* d_err, hipStream_t s);
 
 // ---- gather.hip -----------------------------------------------------------

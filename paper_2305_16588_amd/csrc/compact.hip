@@ -1,22 +1,13 @@
 // Frontier / gather-set dedup (implied by Sec. 4.2.2: each vertex of a mini-batch's
-// sample result counts once).  The sampler stores a 1 into a byte map, one byte per
-// vertex: plain stores, because device-scope atomics on this multi-die GPU are executed
-// at the memory side (about 32 bytes of HBM traffic each) and were the sampler's
-// bottleneck when a bit map was used.  This file turns the byte map into the ascending
-// list of marked vertices -- the sorted-unique order without any sort.
-//
-// One workgroup covers kChunkIds vertices; each of its 4 waves owns a contiguous quarter
-// and reads it in coalesced 16-byte pieces (16 flags per lane per step).  A first kernel
-// counts marks per chunk; the second sums the counts of the chunks before it, ranks its
-// own marks with wave scans and writes the ids.  It also clears the map and, if asked,
-// copies the marks into the gather-set map and bumps a per-vertex counter.
+// sample result counts once).  The sampler sets one bit per sampled vertex; this file
+// turns the bitmap into the ascending list of set bits, which is the sorted-unique
+// order without any sort.  One workgroup covers kChunkBits vertices; a first kernel
+// counts set bits per chunk, a second sums the counts of the chunks before it, scans
+// its own 256 per-thread counts and writes the ids.
 #include "common.hpp"
 
 namespace lgp {
 namespace {
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-constexpr int kSteps = int(kChunkIds / 4 / (64 * 16));   // 16-byte pieces per lane per wave = 16
 
 __device__ __forceinline__ int wave_inclusive_scan(int x) {
   const int lane = threadIdx.x & 63;
@@ -28,96 +19,77 @@ __device__ __forceinline__ int wave_inclusive_scan(int x) {
   return x;
 }
 
-// 16 flag bytes (each 0 or 1) -> 16-bit mask, bit k = byte k.
-__device__ __forceinline__ uint32_t flags_to_mask(u32x4 v) {
-  const uint32_t a = (v.x * 0x01020408u) >> 24, b = (v.y * 0x01020408u) >> 24;
-  const uint32_t c = (v.z * 0x01020408u) >> 24, d = (v.w * 0x01020408u) >> 24;
-  return (a & 15u) | ((b & 15u) << 4) | ((c & 15u) << 8) | ((d & 15u) << 12);
-}
-
-__device__ __forceinline__ int block_sum(int x, int* lds4) {
+// Exclusive scan of one int per thread over a 256-thread workgroup; *total = sum.
+__device__ __forceinline__ int block_exclusive_scan(int x, int* total) {
+  __shared__ int wave_sum[4];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int inc = wave_inclusive_scan(x);
-  if (lane == 63) lds4[wave] = inc;
+  if (lane == 63) wave_sum[wave] = inc;
   __syncthreads();
-  const int total = lds4[0] + lds4[1] + lds4[2] + lds4[3];
+  int before = 0, all = 0;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const int sw = wave_sum[w];
+    if (w < wave) before += sw;
+    all += sw;
+  }
   __syncthreads();
-  return total;
+  *total = all;
+  return before + inc - x;
 }
 
-__global__ __launch_bounds__(kCompactThreads) void count_marks_kernel(const uint8_t* __restrict__ map,
-                                                                      int32_t* __restrict__ chunk_counts) {
-  __shared__ int lds4[4];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const u32x4* p = reinterpret_cast<const u32x4*>(map + int64_t(blockIdx.x) * kChunkIds + int64_t(wave) * (kChunkIds / 4));
+__global__ __launch_bounds__(kCompactThreads) void count_bits_kernel(const uint64_t* __restrict__ bits,
+                                                                     int32_t* __restrict__ chunk_counts) {
+  const uint64_t* w = bits + int64_t(blockIdx.x) * kChunkWords + int64_t(threadIdx.x) * kWordsPerThread;
   int c = 0;
 #pragma unroll
-  for (int k = 0; k < kSteps; ++k) c += __popc(flags_to_mask(p[k * 64 + lane]));
-  const int total = block_sum(c, lds4);
+  for (int q = 0; q < kWordsPerThread; ++q) c += __popcll(w[q]);
+  int total;
+  block_exclusive_scan(c, &total);
   if (threadIdx.x == 0) chunk_counts[blockIdx.x] = total;
 }
 
 template <bool WITH_OUT>
-__global__ __launch_bounds__(kCompactThreads) void emit_marks_kernel(
-    uint8_t* __restrict__ map, uint8_t* __restrict__ or_into, const int32_t* __restrict__ chunk_counts,
+__global__ __launch_bounds__(kCompactThreads) void emit_bits_kernel(
+    uint64_t* __restrict__ bits, uint64_t* __restrict__ or_into, const int32_t* __restrict__ chunk_counts,
     int32_t* __restrict__ out, int64_t out_cap, int32_t* __restrict__ n_out, uint32_t* __restrict__ bump,
     uint32_t* __restrict__ d_err) {
-  __shared__ int lds4[4];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int64_t id_base = int64_t(blockIdx.x) * kChunkIds + int64_t(wave) * (kChunkIds / 4);
-  u32x4* p = reinterpret_cast<u32x4*>(map + id_base);
-  u32x4 v[kSteps];
-  uint32_t m[kSteps];
+  const int64_t word0 = int64_t(blockIdx.x) * kChunkWords + int64_t(threadIdx.x) * kWordsPerThread;
+  uint64_t w[kWordsPerThread];
   int c = 0;
 #pragma unroll
-  for (int k = 0; k < kSteps; ++k) v[k] = p[k * 64 + lane];
-#pragma unroll
-  for (int k = 0; k < kSteps; ++k) {
-    m[k] = flags_to_mask(v[k]);
-    c += __popc(m[k]);
+  for (int q = 0; q < kWordsPerThread; ++q) {
+    w[q] = bits[word0 + q];
+    c += __popcll(w[q]);
   }
   int64_t pos = 0;
   if (WITH_OUT) {
     int part = 0;
     for (int k = threadIdx.x; k < int(blockIdx.x); k += kCompactThreads) part += chunk_counts[k];
-    const int before_chunks = block_sum(part, lds4);
-    const int wave_total = __shfl(wave_inclusive_scan(c), 63, 64);
-    if (lane == 0) lds4[wave] = wave_total;
-    __syncthreads();
-    int before_waves = 0;
-    for (int w = 0; w < wave; ++w) before_waves += lds4[w];
+    int before_chunks, mine_total;
+    block_exclusive_scan(part, &before_chunks);
+    const int excl = block_exclusive_scan(c, &mine_total);
+    pos = int64_t(before_chunks) + excl;
     if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
-      const int64_t total = int64_t(before_chunks) + lds4[0] + lds4[1] + lds4[2] + lds4[3];
+      const int64_t total = int64_t(before_chunks) + mine_total;
       *n_out = int32_t(total <= out_cap ? total : out_cap);
       if (total > out_cap) atomicOr(d_err, ERR_OVERRUN);
     }
-    pos = int64_t(before_chunks) + before_waves;
-    if (wave_total == 0) return;
   }
+  if (c == 0) return;
 #pragma unroll
-  for (int k = 0; k < kSteps; ++k) {
-    const int ck = __popc(m[k]);
-    int64_t my = pos;
-    if (WITH_OUT) {
-      const int inc = wave_inclusive_scan(ck);
-      my = pos + inc - ck;
-      pos += __shfl(inc, 63, 64);
-    }
-    if (m[k] == 0) continue;
-    const int64_t piece = int64_t(k) * 64 + lane;
-    if (or_into) {
-      u32x4* q = reinterpret_cast<u32x4*>(or_into + id_base) + piece;
-      *q = *q | v[k];
-    }
-    p[piece] = u32x4{0u, 0u, 0u, 0u};
-    uint32_t x = m[k];
-    const int64_t id0 = id_base + piece * 16;
+  for (int q = 0; q < kWordsPerThread; ++q) {
+    uint64_t x = w[q];
+    if (x == 0) continue;
+    if (or_into) or_into[word0 + q] |= x;
+    bits[word0 + q] = 0;
+    const int64_t id0 = (word0 + q) * 64;
     while (x) {
-      const int b = __ffs(int(x)) - 1;
+      const int b = __ffsll((unsigned long long)x) - 1;
       const int32_t id = int32_t(id0 + b);
       if (WITH_OUT) {
-        if (my < out_cap) out[my] = id;
-        ++my;
+        if (pos < out_cap) out[pos] = id;
+        ++pos;
       }
       if (bump) atomicAdd(&bump[id], 1u);
       x &= x - 1;
@@ -127,15 +99,15 @@ __global__ __launch_bounds__(kCompactThreads) void emit_marks_kernel(
 
 }  // namespace
 
-void launch_compact(const DeviceInfo& di, uint8_t* map, uint8_t* or_into, int64_t n_chunks, int32_t* chunk_counts,
+void launch_compact(const DeviceInfo& di, uint64_t* bits, uint64_t* or_into, int64_t n_chunks, int32_t* chunk_counts,
                     int32_t* out, int64_t out_cap, int32_t* n_out, uint32_t* bump, uint32_t* d_err, hipStream_t s) {
   (void)di;
   if (n_out) {
-    hipLaunchKernelGGL(count_marks_kernel, dim3(unsigned(n_chunks)), dim3(kCompactThreads), 0, s, map, chunk_counts);
-    hipLaunchKernelGGL((emit_marks_kernel<true>), dim3(unsigned(n_chunks)), dim3(kCompactThreads), 0, s, map, or_into,
+    hipLaunchKernelGGL(count_bits_kernel, dim3(unsigned(n_chunks)), dim3(kCompactThreads), 0, s, bits, chunk_counts);
+    hipLaunchKernelGGL((emit_bits_kernel<true>), dim3(unsigned(n_chunks)), dim3(kCompactThreads), 0, s, bits, or_into,
                        chunk_counts, out, out_cap, n_out, bump, d_err);
   } else {
-    hipLaunchKernelGGL((emit_marks_kernel<false>), dim3(unsigned(n_chunks)), dim3(kCompactThreads), 0, s, map,
+    hipLaunchKernelGGL((emit_bits_kernel<false>), dim3(unsigned(n_chunks)), dim3(kCompactThreads), 0, s, bits,
                        or_into, chunk_counts, out, out_cap, n_out, bump, d_err);
   }
 }
