@@ -34,7 +34,7 @@ typedef enum {
   LGP_EINVAL = -1,       /* null pointer, negative size, id out of range, bad dtype width        */
   LGP_ESTATE = -2,       /* call order: e.g. build_cache before any hotness exists                */
   LGP_ECAPACITY = -3,    /* a caller buffer is smaller than the worst case for this call          */
-  LGP_EUNSUPPORTED = -4, /* fanout > LGP_MAX_FANOUT, hops > LGP_MAX_HOPS, V >= 2^31, row too wide  */
+  LGP_EUNSUPPORTED = -4, /* fanout > LGP_MAX_FANOUT, hops > LGP_MAX_HOPS, V >= 2^31, E >= 2^39, row too wide */
   LGP_EHIP = -5,         /* a HIP runtime call failed; lgp_last_error has the text                */
   LGP_ENOMEM = -6,       /* device or pinned allocation failed                                    */
   LGP_EDEVICE = -7       /* a kernel met an invalid vertex id or overran a buffer (sticky flag)   */
@@ -97,17 +97,20 @@ int lgp_host_alloc(size_t bytes, void** out);
 int lgp_host_free(void* ptr);
 
 /* Create a context for `g` on GPU `device`.  Validates sizes and pointer kinds
- * (LGP_EINVAL if an array is not GPU-addressable), allocates two empty remap
- * tables, two hotness vectors and the dedup bitmaps (about 16.3 bytes per vertex)
- * and starts with empty caches, so sampling and gathering already work, entirely
- * from CPU memory (the "topology in CPU memory" mode of Sec. 3.2).  Synchronous. */
+ * (LGP_EINVAL if an array is not GPU-addressable) and allocates the per-vertex
+ * lookup state in HBM: a row table (offset + degree + "cached" flag, 8 bytes per
+ * vertex, filled from indptr), the feature remap, two hotness vectors and the dedup
+ * bitmaps -- about 20.3 bytes per vertex, outside the cache budgets.  It starts with
+ * empty caches, so sampling and gathering already work, with every column id and
+ * feature row read from CPU memory (the "topology in CPU memory" mode of Sec. 3.2).
+ * Synchronous. */
 int lgp_create(const lgp_graph* g, int device, lgp_ctx** out);
 int lgp_destroy(lgp_ctx* ctx);
 
 /* Pre-sampling (Sec. 4.2.2, step S1).  The tablet train_ids [device, n_train ids,
  * already in epoch order] is cut into consecutive mini-batches of `batch` seeds (the
- * last may be short); batch b is sampled with rng seed base_seed + b, reading all
- * topology from CPU memory.  For every expanded vertex its topology hotness grows by
+ * last may be short); batch b is sampled with rng seed base_seed + b; column ids come
+ * from CPU memory unless a topology cache was built before.  For every expanded vertex its topology hotness grows by
  * the number of edges sampled out of it; for every distinct vertex of a batch's
  * result (seeds included) its feature hotness grows by one.  Both vectors are reset
  * first.  max_batches < 0 processes the whole tablet once.  fanouts is [host]. */

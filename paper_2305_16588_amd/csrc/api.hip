@@ -27,7 +27,7 @@ struct lgp_ctx {
   int64_t row_bytes = 0;
   int64_t n_chunks = 0;    // dedup bitmap chunks
 
-  int32_t* t_remap = nullptr;
+  uint64_t* row_tab = nullptr;   // per-vertex (cached?, offset, degree)
   int32_t* f_remap = nullptr;
   uint32_t* topo_hot = nullptr;
   uint32_t* feat_hot = nullptr;
@@ -126,12 +126,11 @@ void free_cache(lgp_ctx* c) {
   c->plan = CachePlan();
 }
 
-TopoView topo_view(const lgp_ctx* c, bool use_cache) {
+TopoView topo_view(const lgp_ctx* c) {
   TopoView tv;
+  tv.row_tab = c->row_tab;
   tv.h_indptr = c->g.indptr;
   tv.h_indices = c->g.indices;
-  tv.t_remap = (use_cache && c->plan.n_topo > 0) ? c->t_remap : nullptr;
-  tv.t_indptr = c->t_indptr;
   tv.t_indices = c->t_indices;
   tv.indptr_bytes = c->g.indptr_bytes;
   tv.num_vertices = c->g.num_vertices;
@@ -195,7 +194,7 @@ int sample_core(lgp_ctx* c, const int32_t* seeds, int32_t n_seeds, const int32_t
   uint32_t* fbits32 = reinterpret_cast<uint32_t*>(c->fbits);
   uint32_t* gbits32 = reinterpret_cast<uint32_t*>(c->gbits);
   int32_t* n_frontier = hot_mode ? c->hs_n : out->n_frontier;
-  const TopoView tv = topo_view(c, !hot_mode);
+  const TopoView tv = topo_view(c);
 
   launch_mark_ids(c->di, seeds, n_seeds, V, gbits32, n_frontier, c->d_err, s);
   const int32_t* frontier = seeds;
@@ -316,7 +315,7 @@ int lgp_create(const lgp_graph* g, int device, lgp_ctx** out) {
   *out = nullptr;
   if (g->num_vertices < 1 || g->num_edges < 0 || !g->indptr || (g->num_edges > 0 && !g->indices)) return LGP_EINVAL;
   if (g->indptr_bytes != 4 && g->indptr_bytes != 8) return LGP_EINVAL;
-  if (g->num_vertices >= (int64_t(1) << 31)) return LGP_EUNSUPPORTED;
+  if (g->num_vertices >= (int64_t(1) << 31) || g->num_edges >= (int64_t(1) << 39)) return LGP_EUNSUPPORTED;
   if (g->features && (g->feat_dim < 1 || g->elem_bytes < 1)) return LGP_EINVAL;
   int n_dev = 0;
   if (hipGetDeviceCount(&n_dev) != hipSuccess || device < 0 || device >= n_dev) {
@@ -359,7 +358,7 @@ int lgp_create(const lgp_graph* g, int device, lgp_ctx** out) {
   auto step = [&](hipError_t r) {
     if (e == hipSuccess) e = r;
   };
-  step(dev_alloc(&c->t_remap, size_t(V)));
+  step(dev_alloc(&c->row_tab, size_t(V)));
   step(dev_alloc(&c->f_remap, size_t(V)));
   step(dev_alloc(&c->topo_hot, size_t(V)));
   step(dev_alloc(&c->feat_hot, size_t(V)));
@@ -369,7 +368,6 @@ int lgp_create(const lgp_graph* g, int device, lgp_ctx** out) {
   step(dev_alloc(&c->d_err, 1));
   step(dev_alloc(&c->counters, 2));
   step(dev_alloc(&c->hs_n, LGP_MAX_HOPS));
-  if (e == hipSuccess) e = hipMemset(c->t_remap, 0xff, sizeof(int32_t) * size_t(V));
   if (e == hipSuccess) e = hipMemset(c->f_remap, 0xff, sizeof(int32_t) * size_t(V));
   if (e == hipSuccess) e = hipMemset(c->topo_hot, 0, sizeof(uint32_t) * size_t(V));
   if (e == hipSuccess) e = hipMemset(c->feat_hot, 0, sizeof(uint32_t) * size_t(V));
@@ -380,6 +378,10 @@ int lgp_create(const lgp_graph* g, int device, lgp_ctx** out) {
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->miss_stream, hipStreamNonBlocking);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming);
+  if (e == hipSuccess) {
+    launch_init_row_table(c->di, c->g.indptr, c->g.indptr_bytes, V, c->row_tab, nullptr);
+    e = hipGetLastError();
+  }
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     (void)hipGetLastError();
@@ -394,7 +396,7 @@ int lgp_destroy(lgp_ctx* c) {
   (void)hipSetDevice(c->di.device);
   (void)hipDeviceSynchronize();
   free_cache(c);
-  void* ptrs[] = {c->t_remap, c->f_remap, c->topo_hot, c->feat_hot, c->fbits, c->gbits, c->chunk_counts,
+  void* ptrs[] = {c->row_tab, c->f_remap, c->topo_hot, c->feat_hot, c->fbits, c->gbits, c->chunk_counts,
                   c->d_err,   c->counters, c->order_t, c->order_f,  c->lists, c->hs_n};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
@@ -496,7 +498,7 @@ int lgp_build_cache(lgp_ctx* c, uint64_t topo_budget, uint64_t feat_budget, void
   LGP_HIP(c, hipStreamSynchronize(s));
   LGP_HIP(c, hipStreamSynchronize(c->miss_stream));
   free_cache(c);
-  launch_fill_i32(c->di, c->t_remap, V, -1, s);
+  launch_init_row_table(c->di, c->g.indptr, c->g.indptr_bytes, V, c->row_tab, s);
   launch_fill_i32(c->di, c->f_remap, V, -1, s);
   CachePlan p;
   uint64_t* scan = nullptr;
@@ -509,7 +511,7 @@ int lgp_build_cache(lgp_ctx* c, uint64_t topo_budget, uint64_t feat_budget, void
     launch_topo_offsets(c->di, scan, p.n_topo, c->t_indptr, s);
     launch_fill_topo(c->di, c->g.indptr, c->g.indptr_bytes, c->g.indices, c->order_t, p.n_topo, c->t_indptr,
                      c->t_indices, s);
-    launch_scatter_rank(c->di, c->order_t, p.n_topo, c->t_remap, s);
+    launch_set_cached_rows(c->di, c->order_t, p.n_topo, c->t_indptr, c->row_tab, s);
     if (p.n_feat > 0) {
       launch_gather_rows(c->di, c->g.features, c->fc, c->row_bytes, nullptr, c->order_f, p.n_feat, nullptr, true, s);
       launch_scatter_rank(c->di, c->order_f, p.n_feat, c->f_remap, s);
@@ -521,7 +523,8 @@ int lgp_build_cache(lgp_ctx* c, uint64_t topo_budget, uint64_t feat_budget, void
   if (e != hipSuccess) {
     st = fail_hip(c, e, "cache fill");
     free_cache(c);
-    (void)hipMemset(c->t_remap, 0xff, sizeof(int32_t) * size_t(V));
+    launch_init_row_table(c->di, c->g.indptr, c->g.indptr_bytes, V, c->row_tab, s);
+    (void)hipStreamSynchronize(s);
     (void)hipMemset(c->f_remap, 0xff, sizeof(int32_t) * size_t(V));
     return st;
   }

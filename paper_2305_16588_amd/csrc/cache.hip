@@ -63,6 +63,27 @@ __global__ __launch_bounds__(256) void fill_topo_kernel(const IdxT* __restrict__
   }
 }
 
+template <typename IdxT>
+__global__ void init_row_table_kernel(const IdxT* __restrict__ indptr, int64_t num_vertices,
+                                      uint64_t* __restrict__ row_tab) {
+  for (int64_t v = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; v < num_vertices;
+       v += int64_t(gridDim.x) * blockDim.x) {
+    const uint64_t s = uint64_t(indptr[v]);
+    const uint64_t d = uint64_t(indptr[v + 1]) - s;
+    const uint64_t d24 = d < kRowDegOverflow ? d : kRowDegOverflow;
+    row_tab[v] = ((s & kRowStartMask) << kRowStartShift) | d24;
+  }
+}
+
+__global__ void set_cached_rows_kernel(const int32_t* __restrict__ order, int64_t n_topo,
+                                       const int64_t* __restrict__ t_indptr, uint64_t* __restrict__ row_tab) {
+  for (int64_t r = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; r < n_topo; r += int64_t(gridDim.x) * blockDim.x) {
+    const uint64_t s = uint64_t(t_indptr[r]);
+    const uint64_t d = uint64_t(t_indptr[r + 1]) - s;
+    if (d < kRowDegOverflow) row_tab[order[r]] = kRowCachedBit | ((s & kRowStartMask) << kRowStartShift) | d;
+  }
+}
+
 __global__ void fill_i32_kernel(int32_t* __restrict__ p, int64_t n, int32_t value) {
   for (int64_t k = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; k < n; k += int64_t(gridDim.x) * blockDim.x)
     p[k] = value;
@@ -151,6 +172,23 @@ void launch_fill_topo(const DeviceInfo& di, const void* h_indptr, int32_t indptr
 
 void launch_fill_i32(const DeviceInfo& di, int32_t* p, int64_t n, int32_t value, hipStream_t s) {
   hipLaunchKernelGGL(fill_i32_kernel, dim3(grid_for(di, n)), dim3(256), 0, s, p, n, value);
+}
+
+void launch_init_row_table(const DeviceInfo& di, const void* h_indptr, int32_t indptr_bytes, int64_t num_vertices,
+                           uint64_t* row_tab, hipStream_t s) {
+  if (indptr_bytes == 8)
+    hipLaunchKernelGGL(init_row_table_kernel<int64_t>, dim3(grid_for(di, num_vertices)), dim3(256), 0, s,
+                       static_cast<const int64_t*>(h_indptr), num_vertices, row_tab);
+  else
+    hipLaunchKernelGGL(init_row_table_kernel<int32_t>, dim3(grid_for(di, num_vertices)), dim3(256), 0, s,
+                       static_cast<const int32_t*>(h_indptr), num_vertices, row_tab);
+}
+
+void launch_set_cached_rows(const DeviceInfo& di, const int32_t* order, int64_t n_topo, const int64_t* t_indptr,
+                            uint64_t* row_tab, hipStream_t s) {
+  if (n_topo <= 0) return;
+  hipLaunchKernelGGL(set_cached_rows_kernel, dim3(grid_for(di, n_topo)), dim3(256), 0, s, order, n_topo, t_indptr,
+                     row_tab);
 }
 
 void launch_scatter_rank(const DeviceInfo& di, const int32_t* order, int64_t n, int32_t* remap, hipStream_t s) {

@@ -27,13 +27,22 @@ struct DeviceInfo {
   int miss_blocks = 512;   // grid of the PCIe row gather
 };
 
+// Row table: one 64-bit entry per vertex, resident in HBM, so that finding a vertex's adjacency
+// costs one load whether or not the row is cached.
+//   bit 63      1 = the row's column ids are in the topology cache, 0 = in CPU memory
+//   bits 62..24 offset of the row's first column id inside that array (39 bits)
+//   bits 23..0  degree; kRowDegOverflow means "too large to pack: use the CPU-resident CSR"
+constexpr uint64_t kRowCachedBit = 1ull << 63;
+constexpr uint32_t kRowDegOverflow = 0xFFFFFFu;
+constexpr int kRowStartShift = 24;
+constexpr uint64_t kRowStartMask = (1ull << 39) - 1;
+
 // Pointers every sampling kernel needs.
 struct TopoView {
-  const void* h_indptr;      // CPU-resident CSR (GPU-addressable)
+  const uint64_t* row_tab;   // row table (HBM)
+  const void* h_indptr;      // CPU-resident CSR (GPU-addressable); offsets only read for overflow rows
   const int32_t* h_indices;
-  const int32_t* t_remap;    // vertex -> topology-cache slot, -1 if absent; nullptr = ignore the cache
-  const int64_t* t_indptr;   // cached CSR (HBM)
-  const int32_t* t_indices;
+  const int32_t* t_indices;  // cached column ids (HBM)
   int32_t indptr_bytes;
   int64_t num_vertices;
 };
@@ -96,6 +105,12 @@ void launch_fill_topo(const DeviceInfo& di, const void* h_indptr, int32_t indptr
                       const int32_t* order, int64_t n_topo, const int64_t* t_indptr, int32_t* t_indices,
                       hipStream_t s);
 void launch_fill_i32(const DeviceInfo& di, int32_t* p, int64_t n, int32_t value, hipStream_t s);
+// row_tab[v] = (not cached, CPU offset, degree) for every vertex, streamed from the CPU-resident offsets.
+void launch_init_row_table(const DeviceInfo& di, const void* h_indptr, int32_t indptr_bytes, int64_t num_vertices,
+                           uint64_t* row_tab, hipStream_t s);
+// row_tab[order[r]] = (cached, t_indptr[r], degree) for r < n_topo (rows too long to pack keep their CPU entry).
+void launch_set_cached_rows(const DeviceInfo& di, const int32_t* order, int64_t n_topo, const int64_t* t_indptr,
+                            uint64_t* row_tab, hipStream_t s);
 // remap[order[r]] = r for r < n.
 void launch_scatter_rank(const DeviceInfo& di, const int32_t* order, int64_t n, int32_t* remap, hipStream_t s);
 

@@ -1,8 +1,9 @@
 // Neighbour sampler (Sec. 2.2 step 2; Sec. 5 "neighbor sampler") for gfx950.
 //
 // A group of P = next_pow2(fanout) lanes owns one frontier vertex; lane i is sample
-// slot i.  Row bounds come from the HBM topology cache when the vertex is cached and
-// from the CPU-resident CSR (read in place over PCIe) otherwise.  All slots draw their
+// slot i.  One load of the HBM row table gives the row's offset and degree and says
+// whether its column ids sit in the HBM topology cache or in the CPU-resident CSR (read
+// in place over PCIe), so an uncached vertex costs one PCIe round trip, not two.  All slots draw their
 // Philox number at once; Floyd's sequential "already taken?" test becomes fanout-1
 // group broadcasts.  The kernel is bound by dependent-load latency, so it keeps the
 // register footprint small and the grid at full occupancy.
@@ -14,8 +15,8 @@ namespace {
 
 template <typename IdxT, int P>
 __global__ __launch_bounds__(256) void sample_hop_kernel(
-    const IdxT* __restrict__ h_indptr, const int32_t* __restrict__ h_indices, const int32_t* __restrict__ t_remap,
-    const int64_t* __restrict__ t_indptr, const int32_t* __restrict__ t_indices, int64_t num_vertices,
+    const uint64_t* __restrict__ row_tab, const IdxT* __restrict__ h_indptr, const int32_t* __restrict__ h_indices,
+    const int32_t* __restrict__ t_indices, int64_t num_vertices,
     const int32_t* __restrict__ frontier, const int32_t* __restrict__ n_frontier, int64_t cap, int32_t f, int32_t hop,
     uint32_t k0, uint32_t k1, int32_t* __restrict__ nbr, int32_t* __restrict__ cnt, uint32_t* __restrict__ mark_bits,
     uint32_t* __restrict__ topo_hot, uint32_t* __restrict__ d_err) {
@@ -32,12 +33,13 @@ __global__ __launch_bounds__(256) void sample_hop_kernel(
     int64_t s = 0, d64 = 0;
     const int32_t* colbase = h_indices;
     if (active && !bad) {
-      const int32_t slot = t_remap ? t_remap[v] : -1;
-      if (slot >= 0) {
-        s = t_indptr[slot];
-        d64 = t_indptr[slot + 1] - s;
-        colbase = t_indices;
-      } else {
+      const uint64_t e = row_tab[v];
+      const uint32_t d24 = uint32_t(e) & kRowDegOverflow;
+      if (d24 != kRowDegOverflow) {
+        s = int64_t((e >> kRowStartShift) & kRowStartMask);
+        d64 = d24;
+        if (e & kRowCachedBit) colbase = t_indices;
+      } else {                                     // degree does not fit the entry: CPU-resident CSR
         s = int64_t(h_indptr[v]);
         d64 = int64_t(h_indptr[int64_t(v) + 1]) - s;
       }
@@ -108,7 +110,7 @@ void launch_one(const DeviceInfo& di, const TopoView& tv, const int32_t* frontie
   if (blocks > full) blocks = full;
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL((sample_hop_kernel<IdxT, P>), dim3(unsigned(blocks)), dim3(256), 0, s,
-                     static_cast<const IdxT*>(tv.h_indptr), tv.h_indices, tv.t_remap, tv.t_indptr, tv.t_indices,
+                     tv.row_tab, static_cast<const IdxT*>(tv.h_indptr), tv.h_indices, tv.t_indices,
                      tv.num_vertices, frontier, n_frontier, cap, f, hop, uint32_t(seed), uint32_t(seed >> 32), nbr,
                      cnt, mark_bits, topo_hot, d_err);
 }
