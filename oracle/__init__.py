@@ -75,8 +75,14 @@ def _load():
         L.orc_gather.restype = None
         L.orc_count_hits.argtypes = [vp, i64, vp, i64, i64]
         L.orc_count_hits.restype = i64
+        L.orc_search_cache_plan.argtypes = [gp, vp, vp, vp, vp, i64, u64, u64, C.c_uint32, i32, vp]
+        L.orc_search_cache_plan.restype = i32
         _lib = L
     return _lib
+
+
+PLAN_POINT = np.dtype([("m_topo", np.uint64), ("m_feat", np.uint64), ("n_topo", np.int64), ("n_feat", np.int64),
+                       ("uncached_topo_hot", np.uint64), ("uncached_feat_hot", np.uint64)])
 
 
 def _p(a: np.ndarray) -> int:
@@ -187,6 +193,16 @@ class Oracle:
         out = np.empty((ids.size, self.features.shape[1]), dtype=self.features.dtype)
         self._L.orc_gather(_p(self.features), self.row_bytes, _p(ids), ids.size, _p(out) if ids.size else None)
         return out
+
+    def search_cache_plan(self, topo_hot, feat_hot, order_t, order_f, total_budget: int, n_tsum: int, cls: int = 64,
+                          n_alpha: int = 101):
+        """Returns (best_index, points): points is a structured array with one entry per candidate alpha."""
+        topo_hot = np.ascontiguousarray(topo_hot, dtype=np.uint32)
+        feat_hot = np.ascontiguousarray(feat_hot, dtype=np.uint32)
+        points = np.zeros(n_alpha, dtype=PLAN_POINT)
+        best = self._L.orc_search_cache_plan(C.byref(self._g), _p(topo_hot), _p(feat_hot), _p(order_t), _p(order_f),
+                                             self.row_bytes, int(total_budget), int(n_tsum), cls, n_alpha, _p(points))
+        return int(best), points
 
     def count_hits(self, ids: np.ndarray, order: np.ndarray, n_cached: int) -> int:
         ids = np.ascontiguousarray(ids, dtype=np.int32)

@@ -32,6 +32,12 @@
 //     whose features are extracted is the ascending sorted union of the seeds
 //     and all sampled neighbours.
 //
+//   * cache plan search (Sec. 4.3): for alpha = 0, 1/(n-1), ..., 1 the topology cache gets
+//     m_T = floor(B * alpha) bytes and the feature cache B - m_T; N_total = N_T + N_F with
+//     Eq. 3-8, the plan with the smallest N_total wins (paper silent on ties: smallest
+//     alpha).  N_T is a ratio of integers, so plans are compared exactly by cross
+//     multiplication instead of in floating point.
+//
 // Every function has a pin in tests/ (known-answer vectors, brute force,
 // closed forms or library routines); none is "parity unpinned".
 
@@ -297,6 +303,65 @@ int64_t orc_count_hits(const int32_t* ids, int64_t n, const int32_t* order, int6
   int64_t hits = 0;
   for (int64_t i = 0; i < n; ++i) hits += cached[ids[i]];
   return hits;
+}
+
+// --- cost model and alpha search (Sec. 4.3.2 Eq. 2-8, Sec. 4.3.3) -----------
+struct orc_plan_point {
+  uint64_t m_topo, m_feat;          // bytes given to the two caches at this alpha
+  int64_t n_topo, n_feat;           // cached vertices (Eq. 3, Eq. 6)
+  uint64_t uncached_topo_hot;       // sum of a_T over vertices outside the topology cache
+  uint64_t uncached_feat_hot;       // U_F of Eq. 7
+};
+
+// Evaluates every candidate plan and returns the index of the best one.  n_tsum is
+// N_TSUM (PCIe transactions the pre-sampling caused for topology); cls is the transfer
+// granularity of Eq. 8.  N_T = n_tsum * uncached_topo_hot / total_topo_hot (Eq. 4-5),
+// N_F = ceil(row_bytes / cls) * uncached_feat_hot (Eq. 8).
+int32_t orc_search_cache_plan(const orc_graph* g, const uint32_t* topo_hot, const uint32_t* feat_hot,
+                              const int32_t* order_t, const int32_t* order_f, int64_t row_bytes,
+                              uint64_t total_budget, uint64_t n_tsum, uint32_t cls, int32_t n_alpha,
+                              orc_plan_point* points) {
+  const Graph G = to_graph(g);
+  const int64_t V = G.num_vertices;
+  uint64_t all_t = 0, all_f = 0;
+  for (int64_t v = 0; v < V; ++v) { all_t += topo_hot[v]; all_f += feat_hot[v]; }
+  const uint64_t per_row = (static_cast<uint64_t>(row_bytes) + cls - 1) / cls;
+  int32_t best = 0;
+  unsigned __int128 best_key = 0;
+  for (int32_t i = 0; i < n_alpha; ++i) {
+    orc_plan_point& p = points[i];
+    p.m_topo = n_alpha > 1 ? static_cast<uint64_t>((static_cast<unsigned __int128>(total_budget) * i) / (n_alpha - 1))
+                           : 0;
+    p.m_feat = total_budget - p.m_topo;
+    // Eq. 3: grow the topology cache along Q_T while it fits
+    uint64_t used = 0, cached_t = 0;
+    int64_t n = 0;
+    for (; n < V; ++n) {
+      const int64_t v = order_t[n];
+      const uint64_t cost = static_cast<uint64_t>(row_begin(G, v + 1) - row_begin(G, v)) * 4u + 8u;
+      if (used + cost > p.m_topo) break;
+      used += cost;
+      cached_t += topo_hot[v];
+    }
+    p.n_topo = n;
+    p.uncached_topo_hot = all_t - cached_t;
+    // Eq. 6: feature rows along Q_F while they fit
+    uint64_t used_f = 0, cached_f = 0;
+    int64_t m = 0;
+    for (; m < V; ++m) {
+      if (used_f + static_cast<uint64_t>(row_bytes) > p.m_feat) break;
+      used_f += static_cast<uint64_t>(row_bytes);
+      cached_f += feat_hot[order_f[m]];
+    }
+    p.n_feat = m;
+    p.uncached_feat_hot = all_f - cached_f;
+    // N_total * all_t = n_tsum * uncached_t + N_F * all_t   (all_t == 0: no topology traffic at all)
+    const unsigned __int128 scale = all_t ? all_t : 1;
+    const unsigned __int128 key = (all_t ? static_cast<unsigned __int128>(n_tsum) * p.uncached_topo_hot : 0) +
+                                  static_cast<unsigned __int128>(per_row) * p.uncached_feat_hot * scale;
+    if (i == 0 || key < best_key) { best = i; best_key = key; }
+  }
+  return best;
 }
 
 } // extern "C"
