@@ -135,6 +135,27 @@ int lgp_plan_cache(lgp_ctx* ctx, uint64_t topo_budget, uint64_t feat_budget, lgp
 int lgp_build_cache(lgp_ctx* ctx, uint64_t topo_budget, uint64_t feat_budget, void* stream);
 int lgp_get_cache_plan(lgp_ctx* ctx, lgp_cache_plan* plan);
 
+/* One candidate of the cache-plan search: what alpha = index / (n_alpha - 1) would cache. */
+typedef struct {
+  uint64_t m_topo, m_feat;        /* bytes for the two caches: m_topo = floor(B * alpha), m_feat = B - m_topo */
+  int64_t n_topo, n_feat;         /* cached vertices under Eq. 3 / Eq. 6                                      */
+  uint64_t uncached_topo_hot;     /* sum of topology hotness outside the cache; N_T = N_TSUM * this / total   */
+  uint64_t uncached_feat_hot;     /* U_F of Eq. 7; N_F = ceil(row_bytes / CLS) * this                          */
+} lgp_plan_point;
+
+/* Automatic cache management (Sec. 4.3): evaluate the cost model N_total = N_T + N_F
+ * (Eq. 2-8) for alpha = 0, 1/(n_alpha-1), ..., 1 with inclusive scans along the two
+ * rankings and one binary search per candidate (Sec. 4.3.3), and return the index of the
+ * smallest N_total in *best (ties: smallest alpha; plans are compared exactly, by cross
+ * multiplication).  total_budget is B in bytes, n_tsum the number of PCIe transactions
+ * that topology reads caused during pre-sampling (N_TSUM; the sum of topology hotness is
+ * a software stand-in: one transaction per traversed edge), cls_bytes the transfer
+ * granularity CLS of Eq. 8.  points [host, n_alpha entries, may be NULL] receives every
+ * candidate.  2 <= n_alpha <= 1024.  Needs hotness; must be called before lgp_build_cache
+ * (LGP_ESTATE otherwise).  Synchronous. */
+int lgp_search_cache_plan(lgp_ctx* ctx, uint64_t total_budget, uint64_t n_tsum, uint32_t cls_bytes, int32_t n_alpha,
+                          lgp_plan_point* points, int32_t* best, void* stream);
+
 /* Copy the cache to [host] memory for inspection; any pointer may be NULL.
  * topo_ids[n_topo], t_indptr[n_topo + 1], t_indices[topo_edges], feat_ids[n_feat],
  * feat_rows[n_feat * D * elem_bytes].  Synchronous. */

@@ -36,6 +36,11 @@ class CachePlan(C.Structure):
                 ("n_feat", C.c_int64), ("feat_bytes", C.c_uint64)]
 
 
+class PlanPoint(C.Structure):
+    _fields_ = [("m_topo", C.c_uint64), ("m_feat", C.c_uint64), ("n_topo", C.c_int64), ("n_feat", C.c_int64),
+                ("uncached_topo_hot", C.c_uint64), ("uncached_feat_hot", C.c_uint64)]
+
+
 class _SampleOut(C.Structure):
     _fields_ = [("frontier", C.c_void_p * MAX_HOPS), ("nbr", C.c_void_p * MAX_HOPS), ("cnt", C.c_void_p * MAX_HOPS),
                 ("cap", C.c_int64 * MAX_HOPS), ("n_frontier", C.c_void_p), ("gather_ids", C.c_void_p),
@@ -49,7 +54,7 @@ class Profile(C.Structure):
 
 
 EXPORTS = ["lgp_host_alloc", "lgp_host_free", "lgp_create", "lgp_destroy", "lgp_build_hotness", "lgp_get_hotness",
-           "lgp_set_hotness", "lgp_plan_cache", "lgp_build_cache", "lgp_get_cache_plan", "lgp_get_cache",
+           "lgp_set_hotness", "lgp_plan_cache", "lgp_search_cache_plan", "lgp_build_cache", "lgp_get_cache_plan", "lgp_get_cache",
            "lgp_sample_khop", "lgp_gather_features", "lgp_set_overlap", "lgp_check", "lgp_set_profiling", "lgp_get_profile",
            "lgp_strerror", "lgp_last_error"]
 
@@ -74,6 +79,7 @@ def load_library():
     L.lgp_get_hotness.argtypes = [vp, vp, vp]
     L.lgp_set_hotness.argtypes = [vp, vp, vp]
     L.lgp_plan_cache.argtypes = [vp, u64, u64, C.POINTER(CachePlan), vp]
+    L.lgp_search_cache_plan.argtypes = [vp, u64, u64, C.c_uint32, i32, vp, vp, vp]
     L.lgp_build_cache.argtypes = [vp, u64, u64, vp]
     L.lgp_get_cache_plan.argtypes = [vp, C.POINTER(CachePlan)]
     L.lgp_get_cache.argtypes = [vp, vp, vp, vp, vp, vp]
@@ -239,6 +245,17 @@ class Context:
         p = CachePlan()
         self._ok(self._L.lgp_plan_cache(self._h, int(topo_budget), int(feat_budget), C.byref(p), _stream_ptr(stream)))
         return p
+
+    def search_cache_plan(self, total_budget: int, n_tsum: int, cls_bytes: int = 64, n_alpha: int = 101, stream=None):
+        """Returns (best_index, points): points is a numpy structured array, one entry per candidate alpha."""
+        pts = (PlanPoint * n_alpha)()
+        best = C.c_int32(-1)
+        self._ok(self._L.lgp_search_cache_plan(self._h, int(total_budget), int(n_tsum), cls_bytes, n_alpha,
+                                               C.addressof(pts), C.addressof(best), _stream_ptr(stream)))
+        arr = np.frombuffer(pts, dtype=[("m_topo", np.uint64), ("m_feat", np.uint64), ("n_topo", np.int64),
+                                         ("n_feat", np.int64), ("uncached_topo_hot", np.uint64),
+                                         ("uncached_feat_hot", np.uint64)]).copy()
+        return int(best.value), arr
 
     def build_cache(self, topo_budget: int, feat_budget: int, stream=None) -> CachePlan:
         self._ok(self._L.lgp_build_cache(self._h, int(topo_budget), int(feat_budget), _stream_ptr(stream)))

@@ -488,6 +488,54 @@ int lgp_plan_cache(lgp_ctx* c, uint64_t topo_budget, uint64_t feat_budget, lgp_c
   return LGP_OK;
 }
 
+int lgp_search_cache_plan(lgp_ctx* c, uint64_t total_budget, uint64_t n_tsum, uint32_t cls_bytes, int32_t n_alpha,
+                          lgp_plan_point* points, int32_t* best, void* stream) {
+  if (!c) return LGP_EINVAL;
+  if (!best || cls_bytes < 1) return fail(c, LGP_EINVAL, "best is null or cls_bytes is 0");
+  if (n_alpha < 2 || n_alpha > 1024) return fail(c, LGP_EINVAL, "n_alpha must be in [2, 1024]");
+  if (!c->g.features) return fail(c, LGP_ESTATE, "the graph was created without a feature table");
+  if (c->plan.n_topo > 0 || c->plan.n_feat > 0)
+    return fail(c, LGP_ESTATE, "lgp_search_cache_plan re-ranks the vertices; call it before lgp_build_cache");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  LGP_HIP(c, hipSetDevice(c->di.device));
+  const int64_t V = c->g.num_vertices;
+  CachePlan unused;
+  uint64_t* cost_scan = nullptr;
+  int st = plan_core(c, 0, 0, &unused, &cost_scan, s);      // ranks both lists and scans the Eq. 3 cost
+  if (st != LGP_OK) return st;
+  std::vector<uint64_t> m_topo(n_alpha);
+  for (int32_t i = 0; i < n_alpha; ++i)
+    m_topo[i] = uint64_t((static_cast<unsigned __int128>(total_budget) * uint64_t(i)) / uint64_t(n_alpha - 1));
+  uint64_t *hot_t = nullptr, *hot_f = nullptr, *d_m = nullptr;
+  lgp_plan_point* d_points = nullptr;
+  int32_t* d_best = nullptr;
+  std::vector<lgp_plan_point> host_points(n_alpha);
+  hipError_t e = dev_alloc(&hot_t, size_t(V));
+  if (e == hipSuccess) e = dev_alloc(&hot_f, size_t(V));
+  if (e == hipSuccess) e = dev_alloc(&d_m, size_t(n_alpha));
+  if (e == hipSuccess) e = dev_alloc(&d_points, size_t(n_alpha));
+  if (e == hipSuccess) e = dev_alloc(&d_best, 1);
+  if (e == hipSuccess) e = scan_hotness(c->topo_hot, c->order_t, V, hot_t, s);
+  if (e == hipSuccess) e = scan_hotness(c->feat_hot, c->order_f, V, hot_f, s);
+  if (e == hipSuccess) e = hipMemcpyAsync(d_m, m_topo.data(), sizeof(uint64_t) * n_alpha, hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) {
+    const uint64_t per_row = (uint64_t(c->row_bytes) + cls_bytes - 1) / cls_bytes;
+    launch_alpha_search(cost_scan, hot_t, hot_f, V, uint64_t(c->row_bytes), d_m, total_budget, n_tsum, per_row,
+                        n_alpha, d_points, d_best, s);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess)
+    e = hipMemcpyAsync(host_points.data(), d_points, sizeof(lgp_plan_point) * n_alpha, hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess) e = hipMemcpyAsync(best, d_best, sizeof(int32_t), hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  for (void* p : {static_cast<void*>(hot_t), static_cast<void*>(hot_f), static_cast<void*>(d_m),
+                  static_cast<void*>(d_points), static_cast<void*>(d_best), static_cast<void*>(cost_scan)})
+    if (p) (void)hipFree(p);
+  if (e != hipSuccess) return fail_hip(c, e, "cache plan search");
+  if (points) std::memcpy(points, host_points.data(), sizeof(lgp_plan_point) * n_alpha);
+  return LGP_OK;
+}
+
 int lgp_build_cache(lgp_ctx* c, uint64_t topo_budget, uint64_t feat_budget, void* stream) {
   if (!c) return LGP_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);

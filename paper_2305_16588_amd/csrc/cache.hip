@@ -19,6 +19,65 @@ struct TopoCost {
   __host__ __device__ uint64_t operator()(int64_t r) const { return uint64_t(deg[order[r]]) * 4u + 8u; }
 };
 
+struct HotAlong {
+  const uint32_t* hot;
+  const int32_t* order;
+  __host__ __device__ uint64_t operator()(int64_t r) const { return uint64_t(hot[order[r]]); }
+};
+
+struct U128 {
+  uint64_t hi, lo;
+};
+__device__ __forceinline__ U128 mul64(uint64_t a, uint64_t b) { return U128{__umul64hi(a, b), a * b}; }
+__device__ __forceinline__ U128 add128(U128 a, U128 b) {
+  const uint64_t lo = a.lo + b.lo;
+  return U128{a.hi + b.hi + (lo < a.lo ? 1u : 0u), lo};
+}
+__device__ __forceinline__ bool less128(U128 a, U128 b) { return a.hi < b.hi || (a.hi == b.hi && a.lo < b.lo); }
+
+// Cost model of Sec. 4.3.2 for every candidate alpha at once (Sec. 4.3.3): thread i owns plan i.
+__global__ __launch_bounds__(1024) void alpha_search_kernel(
+    const uint64_t* __restrict__ cost_scan, const uint64_t* __restrict__ hot_t_scan,
+    const uint64_t* __restrict__ hot_f_scan, int64_t num_vertices, uint64_t row_bytes,
+    const uint64_t* __restrict__ m_topo, uint64_t total_budget, uint64_t n_tsum, uint64_t per_row, int32_t n_alpha,
+    lgp_plan_point* __restrict__ points, int32_t* __restrict__ best) {
+  __shared__ uint64_t key_hi[1024], key_lo[1024];
+  const int i = threadIdx.x;
+  const uint64_t all_t = hot_t_scan[num_vertices - 1], all_f = hot_f_scan[num_vertices - 1];
+  if (i < n_alpha) {
+    const uint64_t mt = m_topo[i], mf = total_budget - mt;
+    int64_t lo = 0, hi = num_vertices;           // Eq. 3: rows of Q_T whose running cost stays within m_T
+    while (lo < hi) {
+      const int64_t mid = lo + (hi - lo) / 2;
+      if (cost_scan[mid] <= mt) lo = mid + 1;
+      else hi = mid;
+    }
+    const int64_t n_t = lo;
+    uint64_t rows_f = mf / row_bytes;             // Eq. 6
+    const int64_t n_f = rows_f < uint64_t(num_vertices) ? int64_t(rows_f) : num_vertices;
+    const uint64_t unc_t = all_t - (n_t ? hot_t_scan[n_t - 1] : 0);   // Eq. 4 numerator, complemented
+    const uint64_t unc_f = all_f - (n_f ? hot_f_scan[n_f - 1] : 0);   // Eq. 7
+    points[i].m_topo = mt;
+    points[i].m_feat = mf;
+    points[i].n_topo = n_t;
+    points[i].n_feat = n_f;
+    points[i].uncached_topo_hot = unc_t;
+    points[i].uncached_feat_hot = unc_f;
+    // N_total * all_t = n_tsum * unc_t + (per_row * unc_f) * all_t      (Eq. 2, 5, 8)
+    U128 key = mul64(per_row * unc_f, all_t ? all_t : 1);
+    if (all_t) key = add128(key, mul64(n_tsum, unc_t));
+    key_hi[i] = key.hi;
+    key_lo[i] = key.lo;
+  }
+  __syncthreads();
+  if (i == 0) {
+    int b = 0;
+    for (int k = 1; k < n_alpha; ++k)
+      if (less128(U128{key_hi[k], key_lo[k]}, U128{key_hi[b], key_lo[b]})) b = k;
+    *best = b;
+  }
+}
+
 template <typename IdxT>
 __global__ void degrees_kernel(const IdxT* __restrict__ indptr, int64_t num_vertices, int32_t* __restrict__ deg) {
   for (int64_t v = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; v < num_vertices;
@@ -145,6 +204,29 @@ hipError_t scan_topo_cost(const int32_t* deg, const int32_t* order, int64_t num_
   if (e == hipSuccess) e = hipStreamSynchronize(s);
   if (temp) (void)hipFree(temp);
   return e;
+}
+
+hipError_t scan_hotness(const uint32_t* hot, const int32_t* order, int64_t num_vertices, uint64_t* hot_scan,
+                        hipStream_t s) {
+  auto in = rocprim::make_transform_iterator(rocprim::counting_iterator<int64_t>(0), HotAlong{hot, order});
+  void* temp = nullptr;
+  size_t temp_bytes = 0;
+  hipError_t e = rocprim::inclusive_scan(nullptr, temp_bytes, in, hot_scan, size_t(num_vertices),
+                                         rocprim::plus<uint64_t>(), s);
+  if (e == hipSuccess) e = hipMalloc(&temp, temp_bytes ? temp_bytes : 16);
+  if (e == hipSuccess)
+    e = rocprim::inclusive_scan(temp, temp_bytes, in, hot_scan, size_t(num_vertices), rocprim::plus<uint64_t>(), s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (temp) (void)hipFree(temp);
+  return e;
+}
+
+void launch_alpha_search(const uint64_t* cost_scan, const uint64_t* hot_t_scan, const uint64_t* hot_f_scan,
+                         int64_t num_vertices, uint64_t row_bytes, const uint64_t* m_topo, uint64_t total_budget,
+                         uint64_t n_tsum, uint64_t per_row, int32_t n_alpha, lgp_plan_point* points, int32_t* best,
+                         hipStream_t s) {
+  hipLaunchKernelGGL(alpha_search_kernel, dim3(1), dim3(1024), 0, s, cost_scan, hot_t_scan, hot_f_scan, num_vertices,
+                     row_bytes, m_topo, total_budget, n_tsum, per_row, n_alpha, points, best);
 }
 
 void launch_prefix_within_budget(const uint64_t* scan, int64_t n, uint64_t budget, uint64_t* result, hipStream_t s) {

@@ -104,6 +104,15 @@ void launch_topo_offsets(const DeviceInfo& di, const uint64_t* cost_scan, int64_
 void launch_fill_topo(const DeviceInfo& di, const void* h_indptr, int32_t indptr_bytes, const int32_t* h_indices,
                       const int32_t* order, int64_t n_topo, const int64_t* t_indptr, int32_t* t_indices,
                       hipStream_t s);
+// Inclusive scan of hot[order[r]] along a ranking (64-bit sums); hot_scan has V entries.
+hipError_t scan_hotness(const uint32_t* hot, const int32_t* order, int64_t num_vertices, uint64_t* hot_scan,
+                        hipStream_t s);
+// One thread per candidate plan: boundary of Eq. 3 by binary search in the cost scan, Eq. 6 by
+// division, sums from the hotness scans, exact 128-bit comparison key; *best = first smallest key.
+void launch_alpha_search(const uint64_t* cost_scan, const uint64_t* hot_t_scan, const uint64_t* hot_f_scan,
+                         int64_t num_vertices, uint64_t row_bytes, const uint64_t* m_topo, uint64_t total_budget,
+                         uint64_t n_tsum, uint64_t per_row, int32_t n_alpha, lgp_plan_point* points, int32_t* best,
+                         hipStream_t s);
 void launch_fill_i32(const DeviceInfo& di, int32_t* p, int64_t n, int32_t value, hipStream_t s);
 // row_tab[v] = (not cached, CPU offset, degree) for every vertex, streamed from the CPU-resident offsets.
 void launch_init_row_table(const DeviceInfo& di, const void* h_indptr, int32_t indptr_bytes, int64_t num_vertices,

@@ -233,3 +233,25 @@ def test_row_longer_than_the_packed_degree_field():
     assert plan.n_topo == V
     assert_batch_equal(ref, ctx.sample_khop(dev, (12, 3), 99).to_host(dev), "everything cached")
     ctx.check()
+
+
+@pytest.mark.parametrize("B,n_tsum,cls,n_alpha", [(600_000, 3_000_000, 64, 101), (2_000_000, 50_000, 64, 11),
+                                                  (50_000, 10**9, 128, 21), (0, 5, 64, 2), (10**10, 123, 64, 1024),
+                                                  (400_000, 100_000, 64, 101)])
+def test_cache_plan_search(B, n_tsum, cls, n_alpha):
+    """Cost model + alpha search (Sec. 4.3) against the oracle: every candidate and the winner."""
+    from gpu_common import Workload
+    Wl = Workload(datagen.TINY)
+    spec = Wl.spec
+    Wl.ctx.build_hotness(Wl.tablet_dev, spec.batch, spec.fanouts, spec.base_seed)
+    topo, feat = Wl.ctx.get_hotness()
+    qt, qf = Wl.orc.rank_by_hotness(topo), Wl.orc.rank_by_hotness(feat)
+    best, pts = Wl.ctx.search_cache_plan(B, n_tsum, cls, n_alpha)
+    rbest, rpts = Wl.orc.search_cache_plan(topo, feat, qt, qf, B, n_tsum, cls, n_alpha)
+    assert best == rbest
+    for name in rpts.dtype.names:
+        assert (pts[name] == rpts[name]).all(), name
+    # building the chosen plan caches exactly what the search promised
+    plan = Wl.ctx.build_cache(int(pts["m_topo"][best]), int(pts["m_feat"][best]))
+    assert (plan.n_topo, plan.n_feat) == (int(pts["n_topo"][best]), int(pts["n_feat"][best]))
+    Wl.ctx.check()

@@ -30,6 +30,19 @@ def test_presampling_epoch_hotness(W):
     W.hot = (rt, rf)
 
 
+def test_cache_plan_search_on_the_epoch_hotness(W):
+    rt, rf = W.hot
+    qt, qf = W.orc.rank_by_hotness(rt), W.orc.rank_by_hotness(rf)
+    n_tsum = int(rt.sum())                                     # one transaction per traversed edge
+    for B in (400_000_000, 1_200_000_000):
+        best, pts = W.ctx.search_cache_plan(B, n_tsum)
+        rbest, rpts = W.orc.search_cache_plan(rt, rf, qt, qf, B, n_tsum)
+        assert best == rbest and 0 <= best <= 100
+        for name in rpts.dtype.names:
+            assert (pts[name] == rpts[name]).all(), name
+    W.ctx.check()
+
+
 def test_cache_plan_ids_and_contents(W):
     spec = W.spec
     rt, rf = W.hot
