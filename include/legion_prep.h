@@ -160,6 +160,17 @@ typedef struct {
 int lgp_search_cache_plan(lgp_ctx* ctx, uint64_t total_budget, uint64_t n_tsum, uint32_t cls_bytes, int32_t n_alpha,
                           lgp_plan_point* points, int32_t* best, void* stream);
 
+/* Cache candidate selection for a clique of k_g GPUs (Algorithm 1, "Complete Sharing with
+ * Local Preference").  hot [device] is the k_g x V hotness matrix, row-major, one row per
+ * GPU of the clique.  Outputs, all [device] unless noted: acc[V] = column sums (step 1);
+ * order[V] = vertex ids by descending acc, ties by ascending id (step 2); owner[V] = the GPU
+ * with the largest local hotness of each vertex, ties to the lowest GPU index (step 3's
+ * arg-max); queues[V] = the k_g per-GPU queues laid end to end, each in `order` order;
+ * queue_offsets [host, k_g + 1] delimits them.  1 <= k_g <= 64.  With k_g = 1 this is the
+ * plain ranking lgp_build_cache uses.  Needs no context; runs on `device`; synchronous. */
+int lgp_cslp(int device, int32_t k_g, int64_t num_vertices, const uint32_t* hot, uint64_t* acc, int32_t* order,
+             int32_t* owner, int32_t* queues, int64_t* queue_offsets, void* stream);
+
 /* Copy the cache to [host] memory for inspection; any pointer may be NULL.
  * topo_ids[n_topo], t_indptr[n_topo + 1], t_indices[topo_edges], feat_ids[n_feat],
  * feat_rows[n_feat * D * elem_bytes].  Synchronous. */

@@ -77,6 +77,8 @@ def _load():
         L.orc_count_hits.restype = i64
         L.orc_search_cache_plan.argtypes = [gp, vp, vp, vp, vp, i64, u64, u64, C.c_uint32, i32, vp]
         L.orc_search_cache_plan.restype = i32
+        L.orc_cslp.argtypes = [i32, i64, vp, vp, vp, vp, vp, vp]
+        L.orc_cslp.restype = None
         _lib = L
     return _lib
 
@@ -106,6 +108,19 @@ def philox4x32_10(ctr, key) -> np.ndarray:
 
 def draw64(rng_seed: int, v: int, hop: int, slot: int) -> int:
     return int(_load().orc_draw64(rng_seed & (2**64 - 1), v, hop, slot))
+
+
+def cslp(hot: np.ndarray):
+    """Algorithm 1 on a [k_g, V] hotness matrix -> (acc, order, owner, queues, offsets)."""
+    hot = np.ascontiguousarray(hot, dtype=np.uint32)
+    k_g, V = hot.shape
+    acc = np.empty(V, dtype=np.uint64)
+    order = np.empty(V, dtype=np.int32)
+    owner = np.empty(V, dtype=np.int32)
+    queues = np.empty(V, dtype=np.int32)
+    offsets = np.empty(k_g + 1, dtype=np.int64)
+    _load().orc_cslp(k_g, V, _p(hot), _p(acc), _p(order), _p(owner), _p(queues), _p(offsets))
+    return acc, order, owner, queues, offsets
 
 
 @dataclass

@@ -305,6 +305,37 @@ int64_t orc_count_hits(const int32_t* ids, int64_t n, const int32_t* order, int6
   return hits;
 }
 
+// --- Algorithm 1 (CSLP) for a clique of k_g GPUs -----------------------------
+// hot is a k_g x V row-major matrix (one hotness row per GPU).  acc = column sums (step 1),
+// order = vertices by descending acc, ties by ascending id (step 2), owner[v] = GPU with the
+// largest local hotness of v (paper silent on ties: lowest GPU index), queues = the k_g
+// per-GPU queues of step 3 laid end to end, queue g being [offsets[g], offsets[g+1]).
+void orc_cslp(int32_t k_g, int64_t num_vertices, const uint32_t* hot, uint64_t* acc, int32_t* order, int32_t* owner,
+              int32_t* queues, int64_t* offsets) {
+  const int64_t V = num_vertices;
+  for (int64_t v = 0; v < V; ++v) {
+    uint64_t sum = 0;
+    int32_t arg = 0;
+    for (int32_t g = 0; g < k_g; ++g) {
+      const uint32_t h = hot[static_cast<int64_t>(g) * V + v];
+      sum += h;
+      if (h > hot[static_cast<int64_t>(arg) * V + v]) arg = g;
+    }
+    acc[v] = sum;
+    owner[v] = arg;
+    order[v] = static_cast<int32_t>(v);
+  }
+  std::stable_sort(order, order + V, [acc](int32_t a, int32_t b) { return acc[a] > acc[b]; });
+  std::vector<std::vector<int32_t>> G(k_g);
+  for (int64_t r = 0; r < V; ++r) G[owner[order[r]]].push_back(order[r]);
+  int64_t at = 0;
+  for (int32_t g = 0; g < k_g; ++g) {
+    offsets[g] = at;
+    for (int32_t v : G[g]) queues[at++] = v;
+  }
+  offsets[k_g] = at;
+}
+
 // --- cost model and alpha search (Sec. 4.3.2 Eq. 2-8, Sec. 4.3.3) -----------
 struct orc_plan_point {
   uint64_t m_topo, m_feat;          // bytes given to the two caches at this alpha

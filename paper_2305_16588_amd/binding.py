@@ -54,7 +54,7 @@ class Profile(C.Structure):
 
 
 EXPORTS = ["lgp_host_alloc", "lgp_host_free", "lgp_create", "lgp_destroy", "lgp_build_hotness", "lgp_get_hotness",
-           "lgp_set_hotness", "lgp_plan_cache", "lgp_search_cache_plan", "lgp_build_cache", "lgp_get_cache_plan", "lgp_get_cache",
+           "lgp_set_hotness", "lgp_plan_cache", "lgp_search_cache_plan", "lgp_cslp", "lgp_build_cache", "lgp_get_cache_plan", "lgp_get_cache",
            "lgp_sample_khop", "lgp_gather_features", "lgp_set_overlap", "lgp_check", "lgp_set_profiling", "lgp_get_profile",
            "lgp_strerror", "lgp_last_error"]
 
@@ -80,6 +80,7 @@ def load_library():
     L.lgp_set_hotness.argtypes = [vp, vp, vp]
     L.lgp_plan_cache.argtypes = [vp, u64, u64, C.POINTER(CachePlan), vp]
     L.lgp_search_cache_plan.argtypes = [vp, u64, u64, C.c_uint32, i32, vp, vp, vp]
+    L.lgp_cslp.argtypes = [C.c_int, i32, i64, vp, vp, vp, vp, vp, vp, vp]
     L.lgp_build_cache.argtypes = [vp, u64, u64, vp]
     L.lgp_get_cache_plan.argtypes = [vp, C.POINTER(CachePlan)]
     L.lgp_get_cache.argtypes = [vp, vp, vp, vp, vp, vp]
@@ -136,6 +137,25 @@ def worst_case_sizes(num_vertices: int, n_seeds: int, fanouts):
         if h + 1 < len(fanouts):
             need.append(min(num_vertices, samples))
     return need, min(num_vertices, total)
+
+
+def cslp(hot: torch.Tensor, stream=None):
+    """Algorithm 1 on a [k_g, V] int32/uint32 CUDA tensor of hotness rows.
+    Returns (acc int64[V], order, owner, queues int32[V]) as CUDA tensors and the host list of queue offsets."""
+    L = load_library()
+    assert hot.is_cuda and hot.dim() == 2 and hot.is_contiguous() and hot.element_size() == 4
+    k_g, V = hot.shape
+    dev = hot.device
+    acc = torch.empty(V, dtype=torch.int64, device=dev)
+    order = torch.empty(V, dtype=torch.int32, device=dev)
+    owner = torch.empty(V, dtype=torch.int32, device=dev)
+    queues = torch.empty(V, dtype=torch.int32, device=dev)
+    offsets = (C.c_int64 * (k_g + 1))()
+    st = L.lgp_cslp(dev.index or 0, k_g, V, hot.data_ptr(), acc.data_ptr(), order.data_ptr(), owner.data_ptr(),
+                    queues.data_ptr(), C.addressof(offsets), _stream_ptr(stream))
+    if st != 0:
+        raise LegionPrepError(st, L.lgp_strerror(st).decode())
+    return acc, order, owner, queues, list(offsets)
 
 
 class SampleBuffers:

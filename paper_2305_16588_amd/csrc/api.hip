@@ -536,6 +536,35 @@ int lgp_search_cache_plan(lgp_ctx* c, uint64_t total_budget, uint64_t n_tsum, ui
   return LGP_OK;
 }
 
+int lgp_cslp(int device, int32_t k_g, int64_t num_vertices, const uint32_t* hot, uint64_t* acc, int32_t* order,
+             int32_t* owner, int32_t* queues, int64_t* queue_offsets, void* stream) {
+  if (k_g < 1 || num_vertices < 1 || !hot || !acc || !order || !owner || !queues || !queue_offsets) return LGP_EINVAL;
+  if (k_g > 64 || num_vertices >= (int64_t(1) << 31)) return LGP_EUNSUPPORTED;
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess || device < 0 || device >= n_dev || hipSetDevice(device) != hipSuccess) {
+    (void)hipGetLastError();
+    return LGP_EINVAL;
+  }
+  DeviceInfo di;
+  di.device = device;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, device) == hipSuccess) di.num_cus = prop.multiProcessorCount;
+  unsigned long long* counts = nullptr;
+  hipError_t e = dev_alloc(&counts, size_t(k_g));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (e == hipSuccess) e = cslp_rank(di, k_g, num_vertices, hot, acc, order, owner, queues, counts, s);
+  unsigned long long host_counts[64] = {};
+  if (e == hipSuccess) e = hipMemcpy(host_counts, counts, sizeof(unsigned long long) * size_t(k_g), hipMemcpyDeviceToHost);
+  if (counts) (void)hipFree(counts);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return e == hipErrorOutOfMemory ? LGP_ENOMEM : LGP_EHIP;
+  }
+  queue_offsets[0] = 0;
+  for (int32_t g = 0; g < k_g; ++g) queue_offsets[g + 1] = queue_offsets[g] + int64_t(host_counts[g]);
+  return LGP_OK;
+}
+
 int lgp_build_cache(lgp_ctx* c, uint64_t topo_budget, uint64_t feat_budget, void* stream) {
   if (!c) return LGP_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);

@@ -78,6 +78,42 @@ __global__ __launch_bounds__(1024) void alpha_search_kernel(
   }
 }
 
+// Algorithm 1 step 1 + the arg-max of step 3: one thread per vertex walks its column.
+__global__ void colsum_argmax_kernel(const uint32_t* __restrict__ hot, int32_t k_g, int64_t num_vertices,
+                                     uint64_t* __restrict__ acc, int32_t* __restrict__ owner) {
+  for (int64_t v = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; v < num_vertices;
+       v += int64_t(gridDim.x) * blockDim.x) {
+    uint64_t sum = 0;
+    uint32_t best = 0;
+    int32_t arg = 0;
+    for (int32_t g = 0; g < k_g; ++g) {
+      const uint32_t h = hot[int64_t(g) * num_vertices + v];
+      sum += h;
+      if (h > best) { best = h; arg = g; }
+    }
+    acc[v] = sum;
+    owner[v] = arg;
+  }
+}
+
+// key[r] = owner of the r-th ranked vertex; also counts queue lengths (LDS histogram per workgroup).
+__global__ __launch_bounds__(256) void owner_along_kernel(const int32_t* __restrict__ owner,
+                                                          const int32_t* __restrict__ order, int64_t num_vertices,
+                                                          uint32_t* __restrict__ key,
+                                                          unsigned long long* __restrict__ counts, int32_t k_g) {
+  __shared__ unsigned int hist[64];
+  if (threadIdx.x < 64) hist[threadIdx.x] = 0;
+  __syncthreads();
+  for (int64_t r = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; r < num_vertices;
+       r += int64_t(gridDim.x) * blockDim.x) {
+    const int32_t g = owner[order[r]];
+    key[r] = uint32_t(g);
+    atomicAdd(&hist[g], 1u);
+  }
+  __syncthreads();
+  if (int(threadIdx.x) < k_g && hist[threadIdx.x]) atomicAdd(&counts[threadIdx.x], (unsigned long long)hist[threadIdx.x]);
+}
+
 template <typename IdxT>
 __global__ void degrees_kernel(const IdxT* __restrict__ indptr, int64_t num_vertices, int32_t* __restrict__ deg) {
   for (int64_t v = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; v < num_vertices;
@@ -227,6 +263,43 @@ void launch_alpha_search(const uint64_t* cost_scan, const uint64_t* hot_t_scan, 
                          hipStream_t s) {
   hipLaunchKernelGGL(alpha_search_kernel, dim3(1), dim3(1024), 0, s, cost_scan, hot_t_scan, hot_f_scan, num_vertices,
                      row_bytes, m_topo, total_budget, n_tsum, per_row, n_alpha, points, best);
+}
+
+hipError_t cslp_rank(const DeviceInfo& di, int32_t k_g, int64_t num_vertices, const uint32_t* hot, uint64_t* acc,
+                     int32_t* order, int32_t* owner, int32_t* queues, unsigned long long* counts, hipStream_t s) {
+  const size_t V = size_t(num_vertices);
+  uint64_t* keys_out = nullptr;
+  uint32_t *okey = nullptr, *okey_out = nullptr;
+  void* temp = nullptr;
+  size_t t1 = 0, t2 = 0;
+  int bits = 1;
+  while ((1 << bits) < k_g) ++bits;
+  hipError_t e = hipMalloc(&keys_out, sizeof(uint64_t) * V);
+  if (e == hipSuccess) e = hipMalloc(&okey, sizeof(uint32_t) * V);
+  if (e == hipSuccess) e = hipMalloc(&okey_out, sizeof(uint32_t) * V);
+  if (e == hipSuccess) e = hipMemsetAsync(counts, 0, sizeof(unsigned long long) * size_t(k_g), s);
+  rocprim::counting_iterator<int32_t> ids(0);
+  if (e == hipSuccess) {
+    hipLaunchKernelGGL(colsum_argmax_kernel, dim3(grid_for(di, num_vertices)), dim3(256), 0, s, hot, k_g,
+                       num_vertices, acc, owner);
+    e = hipGetLastError();
+  }
+  // step 2: stable descending sort of the 64-bit sums -> equal sums keep ascending id order
+  if (e == hipSuccess) e = rocprim::radix_sort_pairs_desc(nullptr, t1, acc, keys_out, ids, order, V, 0, 64, s);
+  // step 3: stable ascending sort by owner over the ranked list -> the per-GPU queues, end to end
+  if (e == hipSuccess) e = rocprim::radix_sort_pairs(nullptr, t2, okey, okey_out, order, queues, V, 0, bits, s);
+  if (e == hipSuccess) e = hipMalloc(&temp, (t1 > t2 ? t1 : t2) + 16);
+  if (e == hipSuccess) e = rocprim::radix_sort_pairs_desc(temp, t1, acc, keys_out, ids, order, V, 0, 64, s);
+  if (e == hipSuccess) {
+    hipLaunchKernelGGL(owner_along_kernel, dim3(grid_for(di, num_vertices)), dim3(256), 0, s, owner, order,
+                       num_vertices, okey, counts, k_g);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) e = rocprim::radix_sort_pairs(temp, t2, okey, okey_out, order, queues, V, 0, bits, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  for (void* p : {static_cast<void*>(keys_out), static_cast<void*>(okey), static_cast<void*>(okey_out), temp})
+    if (p) (void)hipFree(p);
+  return e;
 }
 
 void launch_prefix_within_budget(const uint64_t* scan, int64_t n, uint64_t budget, uint64_t* result, hipStream_t s) {

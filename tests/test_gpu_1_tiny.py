@@ -255,3 +255,19 @@ def test_cache_plan_search(B, n_tsum, cls, n_alpha):
     plan = Wl.ctx.build_cache(int(pts["m_topo"][best]), int(pts["m_feat"][best]))
     assert (plan.n_topo, plan.n_feat) == (int(pts["n_topo"][best]), int(pts["n_feat"][best]))
     Wl.ctx.check()
+
+
+@pytest.mark.parametrize("k_g,V,hi,seed", [(1, 5000, 6, 0), (2, 100_000, 4, 1), (4, 333_333, 3, 2), (8, 1_000_000, 40, 3),
+                                           (64, 70_001, 2, 4), (3, 1, 9, 5)])
+def test_cslp_algorithm_1(k_g, V, hi, seed):
+    """Algorithm 1 for a clique of k_g GPUs against the oracle (sums, ranking, owners, per-GPU queues)."""
+    import oracle
+    import paper_2305_16588_amd as lgp
+    hot = np.random.default_rng(seed).integers(0, hi, size=(k_g, V)).astype(np.uint32)
+    if V > 10:
+        hot[:, 3] = 2**32 - 1                                   # column sum beyond 32 bits
+    acc, order, owner, queues, offsets = lgp.cslp(torch.from_numpy(hot.view(np.int32)).cuda())
+    racc, rorder, rowner, rqueues, roffsets = oracle.cslp(hot)
+    assert (acc.cpu().numpy().view(np.uint64) == racc).all()
+    assert (order.cpu().numpy() == rorder).all() and (owner.cpu().numpy() == rowner).all()
+    assert offsets == roffsets.tolist() and (queues.cpu().numpy() == rqueues).all()
