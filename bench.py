@@ -208,6 +208,28 @@ def main() -> int:
                      "how": "sample_khop of batch i+1 on a second stream beside gather_features of batch i"}
         del bufs, outs
 
+    # Graph constructor (a widening row, not part of the headline step): time it on the same batches.
+    blocks_ms = None
+    if not args.no_pipeline:
+        bbuf = lgp.SampleBuffers(V, spec.batch, spec.fanouts, last_frontier=True)
+        blk = lgp.BlockBuffers(bbuf)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        total = 0.0
+        reps = min(args.steps, 20)
+        for i in range(args.warmup, args.warmup + reps + 2):
+            b = i % full_batches
+            seeds = tablet_dev[b * spec.batch:(b + 1) * spec.batch]
+            ctx.sample_khop(seeds, spec.fanouts, spec.base_seed + i, out=bbuf)
+            e0.record()
+            ctx.build_blocks(seeds, spec.fanouts, bbuf, out=blk)
+            e1.record()
+            torch.cuda.synchronize()
+            if i >= args.warmup + 2:
+                total += e0.elapsed_time(e1)
+        blocks_ms = round(total / reps, 4)
+        ctx.check()
+        del bbuf, blk
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -243,6 +265,7 @@ def main() -> int:
                    "cached_topo_rows": plan.n_topo, "cached_feat_rows": plan.n_feat,
                    "batches_in_tablet": n_batches},
         "roofline": roofline, "roofline_pcie": roofline_pcie, "cpu_baseline": cpu, "pipelined": pipelined,
+        "graph_constructor_ms": blocks_ms,
         "per_step": {"gather_rows": round(gathered / args.steps, 1), "hit_rate": round(hit_rows / max(gathered, 1), 4),
                      "ms_sample": round(prof.ms_sample / max(prof.n_sample, 1), 4),
                      "ms_partition": round(prof.ms_partition / max(prof.n_partition, 1), 4),

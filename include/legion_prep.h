@@ -72,19 +72,33 @@ typedef struct {
 } lgp_cache_plan;
 
 /* Destination buffers of one lgp_sample_khop call.  Hop h (0-based) expands frontier h
- * with fan-out fanouts[h]; frontier 0 is the seed list itself.
+ * with fan-out fanouts[h]; frontier 0 is the seed list itself; frontier n_hops is the set
+ * reached by the last hop (never expanded).
  * Worst-case sizes: need[0] = n_seeds, need[h] = min(V, need[h-1] * fanouts[h-1]). */
 typedef struct {
-  int32_t* frontier[LGP_MAX_HOPS]; /* [device] frontier[h], h >= 1: cap[h] ids, ascending, unique; [0] unused */
+  int32_t* frontier[LGP_MAX_HOPS + 1]; /* [device] frontier[h], 1 <= h <= n_hops: cap[h] ids, ascending, unique;
+                                          [0] unused; frontier[n_hops] may be NULL (last set not wanted)        */
   int32_t* nbr[LGP_MAX_HOPS];      /* [device] nbr[h]: cap[h] * fanouts[h]; row i = samples of frontier[h][i],
                                       -1 padded; rows past n_frontier[h] are left untouched                     */
   int32_t* cnt[LGP_MAX_HOPS];      /* [device] cnt[h]: cap[h]; valid entries in row i = min(deg, fanout)        */
-  int64_t cap[LGP_MAX_HOPS];       /* capacities in vertices; cap[h] >= need[h] or LGP_ECAPACITY                */
-  int32_t* n_frontier;             /* [device] int32[n_hops]: actual frontier sizes (n_frontier[0] = n_seeds)   */
+  int64_t cap[LGP_MAX_HOPS + 1];   /* capacities in vertices; cap[h] >= need[h] or LGP_ECAPACITY                */
+  int32_t* n_frontier;             /* [device] int32[n_hops + 1]: actual frontier sizes (n_frontier[0] = n_seeds;
+                                      the last entry is written only if frontier[n_hops] is given)              */
   int32_t* gather_ids;             /* [device] ascending unique union of seeds and all sampled neighbours       */
   int64_t gather_cap;              /* >= min(V, n_seeds + sum_h need[h] * fanouts[h]) or LGP_ECAPACITY          */
   int32_t* n_gather;               /* [device] int32[1]: number of ids written to gather_ids                    */
 } lgp_sample_out;
+
+/* Destination buffers of lgp_build_blocks: the sampled sub-graph as one bipartite CSR block
+ * per hop, in local numbering (what a GNN layer consumes). */
+typedef struct {
+  int64_t* blk_indptr[LGP_MAX_HOPS];   /* [device] cap[h] + 1: blk_indptr[h][i] = sampled edges of the destinations
+                                          before frontier[h][i]                                                  */
+  int32_t* blk_src[LGP_MAX_HOPS];      /* [device] cap[h] * fanouts[h]: position of each sampled neighbour inside
+                                          frontier[h + 1], destination by destination, in slot order             */
+  int32_t* feat_row[LGP_MAX_HOPS + 1]; /* [device] cap[h]: position of frontier[h][i] inside gather_ids = its row
+                                          in the matrix lgp_gather_features(gather_ids) returns; 0 <= h <= n_hops */
+} lgp_blocks_out;
 
 /* Accumulated HIP-event timings of the per-batch kernels (see lgp_set_profiling). */
 typedef struct {
@@ -188,6 +202,16 @@ int lgp_get_cache(lgp_ctx* ctx, int32_t* topo_ids, int64_t* t_indptr, int32_t* t
  * synchronisation: sizes stay on the device (out->n_frontier, out->n_gather). */
 int lgp_sample_khop(lgp_ctx* ctx, const int32_t* seeds, int32_t n_seeds, const int32_t* fanouts, int32_t n_hops,
                     uint64_t rng_seed, const lgp_sample_out* out, void* stream);
+
+/* Graph constructor (Sec. 5, operator 4: "generating the subgraph based on the sampled
+ * results").  Takes the buffers a finished lgp_sample_khop call filled (same seeds, fanouts
+ * and `sampled`, with sampled->frontier[n_hops] given) and writes, per hop h, a bipartite
+ * block in CSR form whose destinations are frontier h and whose sources are frontier h+1,
+ * plus for every frontier the rows of its vertices in the extracted feature matrix.
+ * Everything is read from device memory; no host synchronisation.  The first call
+ * allocates a V-entry lookup table and a small scan scratch (and synchronises once). */
+int lgp_build_blocks(lgp_ctx* ctx, const int32_t* seeds, int32_t n_seeds, const int32_t* fanouts, int32_t n_hops,
+                     const lgp_sample_out* sampled, const lgp_blocks_out* out, void* stream);
 
 /* Feature extraction (Sec. 2.2 step 3; the feature extractor of Sec. 5):
  * out[i, :] = features[ids[i], :] for i < n, byte for byte.  ids is [device] (any

@@ -57,6 +57,10 @@ def _load():
         L.orc_batch_gather_size.restype = i64
         L.orc_batch_gather_ids.argtypes = [vp]
         L.orc_batch_gather_ids.restype = vp
+        L.orc_block_of_hop.argtypes = [vp, i32, i32, vp, vp]
+        L.orc_block_of_hop.restype = None
+        L.orc_feature_rows.argtypes = [vp, i32, vp]
+        L.orc_feature_rows.restype = None
         L.orc_batch_free.argtypes = [vp]
         L.orc_batch_free.restype = None
         L.orc_build_hotness.argtypes = [gp, vp, i64, i32, vp, i32, u64, i64, vp, vp]
@@ -125,11 +129,15 @@ def cslp(hot: np.ndarray):
 
 @dataclass
 class Batch:
-    """Result of sampling one mini-batch.  frontier[0] is the seed list."""
+    """Result of sampling one mini-batch.  frontier[0] is the seed list; frontier has one more entry than
+    nbr / cnt (the set reached by the last hop).  With blocks=True the graph constructor's output is filled in too."""
     frontier: list = field(default_factory=list)
     nbr: list = field(default_factory=list)       # nbr[h]: [len(frontier[h]), fanouts[h]] int32, -1 padded
     cnt: list = field(default_factory=list)
     gather_ids: np.ndarray = None
+    blk_indptr: list = field(default_factory=list)   # per hop: int64[len(frontier[h]) + 1]
+    blk_src: list = field(default_factory=list)      # per hop: int32[edges], positions inside frontier[h + 1]
+    feat_row: list = field(default_factory=list)     # per frontier: positions inside gather_ids
 
 
 class Oracle:
@@ -154,7 +162,7 @@ class Oracle:
         cnt = self._L.orc_sample_row(C.byref(self._g), v, hop, f, rng_seed & (2**64 - 1), _p(out))
         return out, int(cnt)
 
-    def sample_khop(self, seeds: np.ndarray, fanouts, rng_seed: int) -> Batch:
+    def sample_khop(self, seeds: np.ndarray, fanouts, rng_seed: int, blocks: bool = False) -> Batch:
         seeds = np.ascontiguousarray(seeds, dtype=np.int32)
         fo = np.asarray(fanouts, dtype=np.int32)
         h = self._L.orc_sample_khop(C.byref(self._g), _p(seeds), seeds.size, _p(fo), fo.size, rng_seed & (2**64 - 1))
@@ -165,7 +173,21 @@ class Oracle:
                 b.frontier.append(_copy(self._L.orc_batch_frontier(h, hop), n))
                 b.nbr.append(_copy(self._L.orc_batch_nbr(h, hop), n * int(fo[hop])).reshape(n, int(fo[hop])))
                 b.cnt.append(_copy(self._L.orc_batch_cnt(h, hop), n))
+            n_last = int(self._L.orc_batch_frontier_size(h, fo.size))
+            b.frontier.append(_copy(self._L.orc_batch_frontier(h, fo.size), n_last))
             b.gather_ids = _copy(self._L.orc_batch_gather_ids(h), int(self._L.orc_batch_gather_size(h)))
+            if blocks:
+                for hop in range(fo.size):
+                    n = b.frontier[hop].size
+                    indptr = np.zeros(n + 1, dtype=np.int64)
+                    src = np.empty(int(b.cnt[hop].sum()), dtype=np.int32)
+                    self._L.orc_block_of_hop(h, hop, int(fo[hop]), _p(indptr), _p(src) if src.size else None)
+                    b.blk_indptr.append(indptr)
+                    b.blk_src.append(src)
+                for hop in range(fo.size + 1):
+                    rows = np.empty(b.frontier[hop].size, dtype=np.int32)
+                    self._L.orc_feature_rows(h, hop, _p(rows) if rows.size else None)
+                    b.feat_row.append(rows)
         finally:
             self._L.orc_batch_free(h)
         return b

@@ -131,7 +131,7 @@ int32_t sample_row(const Graph& g, int64_t v, int32_t hop, int32_t f, uint64_t r
 
 struct Batch {
   int32_t n_hops = 0;
-  std::vector<std::vector<int32_t>> frontier; // frontier[h], h = 0..n_hops-1
+  std::vector<std::vector<int32_t>> frontier; // frontier[h], h = 0..n_hops (the last one is never expanded)
   std::vector<std::vector<int32_t>> nbr;      // nbr[h]: frontier[h].size() * fanouts[h]
   std::vector<std::vector<int32_t>> cnt;      // cnt[h]: frontier[h].size()
   std::vector<int32_t> gather_ids;
@@ -146,7 +146,7 @@ void sorted_unique(std::vector<int32_t>& a) {
 void sample_khop(const Graph& g, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops,
                  uint64_t rng_seed, Batch& b) {
   b.n_hops = n_hops;
-  b.frontier.assign(n_hops, {});
+  b.frontier.assign(n_hops + 1, {});
   b.nbr.assign(n_hops, {});
   b.cnt.assign(n_hops, {});
   std::vector<int32_t> all(seeds, seeds + n_seeds);
@@ -168,6 +168,7 @@ void sample_khop(const Graph& g, const int32_t* seeds, int64_t n_seeds, const in
     sorted_unique(next);
     cur.swap(next);
   }
+  b.frontier[n_hops] = cur;
   sorted_unique(all);
   b.gather_ids.swap(all);
 }
@@ -207,6 +208,34 @@ const int32_t* orc_batch_cnt(const void* h, int32_t hop) { return static_cast<co
 int64_t orc_batch_gather_size(const void* h) { return (int64_t) static_cast<const Batch*>(h)->gather_ids.size(); }
 const int32_t* orc_batch_gather_ids(const void* h) { return static_cast<const Batch*>(h)->gather_ids.data(); }
 void orc_batch_free(void* h) { delete static_cast<Batch*>(h); }
+
+// --- graph constructor (Sec. 5, operator 4) ----------------------------------
+// The paper only says the constructor "generates the subgraph based on the sampled
+// results".  Reading used here: hop h becomes a bipartite block in CSR form whose
+// destinations are frontier h (in order) and whose sources are frontier h+1;
+// blk_indptr[i] = number of sampled edges of destinations before i, blk_src[e] = position of
+// the e-th sampled neighbour inside frontier h+1; feat_row[i] = position of frontier h's i-th
+// vertex inside gather_ids, i.e. its row in the extracted feature matrix.
+void orc_block_of_hop(const void* handle, int32_t hop, int32_t fanout, int64_t* blk_indptr, int32_t* blk_src) {
+  const Batch& b = *static_cast<const Batch*>(handle);
+  const std::vector<int32_t>& src_set = b.frontier[hop + 1];
+  int64_t e = 0;
+  blk_indptr[0] = 0;
+  for (size_t i = 0; i < b.frontier[hop].size(); ++i) {
+    for (int32_t k = 0; k < fanout; ++k) {
+      const int32_t u = b.nbr[hop][i * static_cast<size_t>(fanout) + k];
+      if (u < 0) continue;
+      blk_src[e++] = static_cast<int32_t>(std::lower_bound(src_set.begin(), src_set.end(), u) - src_set.begin());
+    }
+    blk_indptr[i + 1] = e;
+  }
+}
+void orc_feature_rows(const void* handle, int32_t hop, int32_t* feat_row) {
+  const Batch& b = *static_cast<const Batch*>(handle);
+  for (size_t i = 0; i < b.frontier[hop].size(); ++i)
+    feat_row[i] = static_cast<int32_t>(std::lower_bound(b.gather_ids.begin(), b.gather_ids.end(), b.frontier[hop][i]) -
+                                       b.gather_ids.begin());
+}
 
 // --- pre-sampling hotness (Sec. 4.2.2, S1) ---------------------------------
 // The tablet is consumed in consecutive slices of `batch` ids (last slice may

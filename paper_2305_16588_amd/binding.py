@@ -42,9 +42,14 @@ class PlanPoint(C.Structure):
 
 
 class _SampleOut(C.Structure):
-    _fields_ = [("frontier", C.c_void_p * MAX_HOPS), ("nbr", C.c_void_p * MAX_HOPS), ("cnt", C.c_void_p * MAX_HOPS),
-                ("cap", C.c_int64 * MAX_HOPS), ("n_frontier", C.c_void_p), ("gather_ids", C.c_void_p),
-                ("gather_cap", C.c_int64), ("n_gather", C.c_void_p)]
+    _fields_ = [("frontier", C.c_void_p * (MAX_HOPS + 1)), ("nbr", C.c_void_p * MAX_HOPS),
+                ("cnt", C.c_void_p * MAX_HOPS), ("cap", C.c_int64 * (MAX_HOPS + 1)), ("n_frontier", C.c_void_p),
+                ("gather_ids", C.c_void_p), ("gather_cap", C.c_int64), ("n_gather", C.c_void_p)]
+
+
+class _BlocksOut(C.Structure):
+    _fields_ = [("blk_indptr", C.c_void_p * MAX_HOPS), ("blk_src", C.c_void_p * MAX_HOPS),
+                ("feat_row", C.c_void_p * (MAX_HOPS + 1))]
 
 
 class Profile(C.Structure):
@@ -55,7 +60,7 @@ class Profile(C.Structure):
 
 EXPORTS = ["lgp_host_alloc", "lgp_host_free", "lgp_create", "lgp_destroy", "lgp_build_hotness", "lgp_get_hotness",
            "lgp_set_hotness", "lgp_plan_cache", "lgp_search_cache_plan", "lgp_cslp", "lgp_build_cache", "lgp_get_cache_plan", "lgp_get_cache",
-           "lgp_sample_khop", "lgp_gather_features", "lgp_set_overlap", "lgp_check", "lgp_set_profiling", "lgp_get_profile",
+           "lgp_sample_khop", "lgp_build_blocks", "lgp_gather_features", "lgp_set_overlap", "lgp_check", "lgp_set_profiling", "lgp_get_profile",
            "lgp_strerror", "lgp_last_error"]
 
 _lib = None
@@ -85,6 +90,7 @@ def load_library():
     L.lgp_get_cache_plan.argtypes = [vp, C.POINTER(CachePlan)]
     L.lgp_get_cache.argtypes = [vp, vp, vp, vp, vp, vp]
     L.lgp_sample_khop.argtypes = [vp, vp, i32, vp, i32, u64, C.POINTER(_SampleOut), vp]
+    L.lgp_build_blocks.argtypes = [vp, vp, i32, vp, i32, C.POINTER(_SampleOut), C.POINTER(_BlocksOut), vp]
     L.lgp_gather_features.argtypes = [vp, vp, i64, vp, vp, vp, vp]
     L.lgp_set_overlap.argtypes = [vp, C.c_int]
     L.lgp_check.argtypes = [vp, vp]
@@ -128,14 +134,13 @@ def _stream_ptr(stream):
 
 
 def worst_case_sizes(num_vertices: int, n_seeds: int, fanouts):
-    """need[h] and the gather-set bound, as the header defines them."""
+    """need[h] for h = 0 .. n_hops and the gather-set bound, as the header defines them."""
     need = [int(n_seeds)]
     total = int(n_seeds)
     for h, f in enumerate(fanouts):
         samples = need[h] * int(f)
         total += samples
-        if h + 1 < len(fanouts):
-            need.append(min(num_vertices, samples))
+        need.append(min(num_vertices, samples))
     return need, min(num_vertices, total)
 
 
@@ -161,15 +166,19 @@ def cslp(hot: torch.Tensor, stream=None):
 class SampleBuffers:
     """Device buffers for one lgp_sample_khop call, sized for the worst case."""
 
-    def __init__(self, num_vertices: int, max_seeds: int, fanouts, device="cuda:0"):
+    def __init__(self, num_vertices: int, max_seeds: int, fanouts, device="cuda:0", last_frontier: bool = False):
+        """last_frontier: also produce frontier[n_hops], the set reached by the last hop (needed by build_blocks)."""
         self.fanouts = [int(f) for f in fanouts]
         self.need, self.gather_cap = worst_case_sizes(num_vertices, max_seeds, self.fanouts)
         dev = torch.device(device)
         L = len(self.fanouts)
+        self.last_frontier = last_frontier
         self.frontier = [None] + [torch.empty(self.need[h], dtype=torch.int32, device=dev) for h in range(1, L)]
+        if last_frontier:
+            self.frontier.append(torch.empty(self.need[L], dtype=torch.int32, device=dev))
         self.nbr = [torch.empty((self.need[h], self.fanouts[h]), dtype=torch.int32, device=dev) for h in range(L)]
         self.cnt = [torch.empty(self.need[h], dtype=torch.int32, device=dev) for h in range(L)]
-        self.n_frontier = torch.zeros(L, dtype=torch.int32, device=dev)
+        self.n_frontier = torch.zeros(L + 1, dtype=torch.int32, device=dev)
         self.gather_ids = torch.empty(self.gather_cap, dtype=torch.int32, device=dev)
         self.n_gather = torch.zeros(1, dtype=torch.int32, device=dev)
         o = _SampleOut()
@@ -178,6 +187,9 @@ class SampleBuffers:
             o.nbr[h] = self.nbr[h].data_ptr()
             o.cnt[h] = self.cnt[h].data_ptr()
             o.cap[h] = self.need[h]
+        if last_frontier:
+            o.frontier[L] = self.frontier[L].data_ptr()
+            o.cap[L] = self.need[L]
         o.n_frontier = self.n_frontier.data_ptr()
         o.gather_ids = self.gather_ids.data_ptr()
         o.gather_cap = self.gather_cap
@@ -187,11 +199,41 @@ class SampleBuffers:
     def to_host(self, seeds: torch.Tensor):
         """Synchronise and return (frontier, nbr, cnt, gather_ids) trimmed to their actual sizes (numpy)."""
         n = self.n_frontier.cpu().tolist()
-        fr = [seeds.cpu().numpy()] + [self.frontier[h][:n[h]].cpu().numpy() for h in range(1, len(n))]
-        nbr = [self.nbr[h][:n[h]].cpu().numpy() for h in range(len(n))]
-        cnt = [self.cnt[h][:n[h]].cpu().numpy() for h in range(len(n))]
+        L = len(self.fanouts)
+        fr = [seeds.cpu().numpy()] + [self.frontier[h][:n[h]].cpu().numpy() for h in range(1, len(self.frontier))]
+        nbr = [self.nbr[h][:n[h]].cpu().numpy() for h in range(L)]
+        cnt = [self.cnt[h][:n[h]].cpu().numpy() for h in range(L)]
         ng = int(self.n_gather.item())
         return fr, nbr, cnt, self.gather_ids[:ng].cpu().numpy()
+
+
+class BlockBuffers:
+    """Device buffers for one lgp_build_blocks call, sized like the SampleBuffers they go with."""
+
+    def __init__(self, sample: SampleBuffers):
+        assert sample.last_frontier, "build_blocks needs SampleBuffers(..., last_frontier=True)"
+        dev = sample.gather_ids.device
+        L = len(sample.fanouts)
+        self.sample = sample
+        self.blk_indptr = [torch.empty(sample.need[h] + 1, dtype=torch.int64, device=dev) for h in range(L)]
+        self.blk_src = [torch.empty(sample.need[h] * sample.fanouts[h], dtype=torch.int32, device=dev) for h in range(L)]
+        self.feat_row = [torch.empty(sample.need[h], dtype=torch.int32, device=dev) for h in range(L + 1)]
+        o = _BlocksOut()
+        for h in range(L):
+            o.blk_indptr[h] = self.blk_indptr[h].data_ptr()
+            o.blk_src[h] = self.blk_src[h].data_ptr()
+        for h in range(L + 1):
+            o.feat_row[h] = self.feat_row[h].data_ptr()
+        self.c_struct = o
+
+    def to_host(self):
+        """Synchronise and return (blk_indptr, blk_src, feat_row) trimmed to their actual sizes (numpy)."""
+        n = self.sample.n_frontier.cpu().tolist()
+        L = len(self.sample.fanouts)
+        indptr = [self.blk_indptr[h][:n[h] + 1].cpu().numpy() for h in range(L)]
+        src = [self.blk_src[h][:int(indptr[h][-1])].cpu().numpy() for h in range(L)]
+        rows = [self.feat_row[h][:n[h]].cpu().numpy() for h in range(L + 1)]
+        return indptr, src, rows
 
 
 class Context:
@@ -307,6 +349,15 @@ class Context:
             out = SampleBuffers(self.num_vertices, seeds.numel(), fo.tolist(), self.device)
         self._ok(self._L.lgp_sample_khop(self._h, seeds.data_ptr(), seeds.numel(), fo.ctypes.data, fo.size,
                                          rng_seed & (2**64 - 1), C.byref(out.c_struct), _stream_ptr(stream)))
+        return out
+
+    def build_blocks(self, seeds: torch.Tensor, fanouts, sample: SampleBuffers, out: BlockBuffers | None = None,
+                     stream=None) -> BlockBuffers:
+        fo = self._fanouts(fanouts)
+        if out is None:
+            out = BlockBuffers(sample)
+        self._ok(self._L.lgp_build_blocks(self._h, seeds.data_ptr(), seeds.numel(), fo.ctypes.data, fo.size,
+                                          C.byref(sample.c_struct), C.byref(out.c_struct), _stream_ptr(stream)))
         return out
 
     def gather_features(self, ids: torch.Tensor, n_dev: torch.Tensor | None = None, out: torch.Tensor | None = None,

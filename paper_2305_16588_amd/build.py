@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "liblegion_prep.so")
-SOURCES = ["sampler.hip", "compact.hip", "gather.hip", "cache.hip", "api.hip"]
+SOURCES = ["sampler.hip", "compact.hip", "gather.hip", "blocks.hip", "cache.hip", "api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-I" + INCLUDE, "-I" + CSRC]

@@ -50,6 +50,11 @@ struct lgp_ctx {
   int32_t* lists = nullptr;
   int64_t list_cap = 0;
 
+  // graph-constructor scratch
+  int32_t* pos_table = nullptr;   // V entries: position of a vertex in the frontier scattered last
+  int64_t* tile_sums = nullptr;
+  int64_t tile_cap = 0;
+
   // pre-sampling scratch
   int32_t* hs_frontier[LGP_MAX_HOPS] = {};
   int64_t hs_cap[LGP_MAX_HOPS] = {};
@@ -148,7 +153,7 @@ int check_fanouts(lgp_ctx* ctx, const int32_t* fanouts, int32_t n_hops) {
   return LGP_OK;
 }
 
-// Worst-case frontier sizes: need[0] = n_seeds, need[h] = min(V, need[h-1] * f[h-1]).
+// Worst-case frontier sizes: need[0] = n_seeds, need[h] = min(V, need[h-1] * f[h-1]), h <= n_hops.
 void worst_case(const lgp_ctx* c, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops, int64_t* need,
                 int64_t* gather_need) {
   const int64_t V = c->g.num_vertices;
@@ -157,7 +162,7 @@ void worst_case(const lgp_ctx* c, int64_t n_seeds, const int32_t* fanouts, int32
   for (int h = 0; h < n_hops; ++h) {
     const int64_t samples = need[h] * fanouts[h];
     total += samples;
-    if (h + 1 < n_hops) need[h + 1] = std::min(V, samples);
+    need[h + 1] = std::min(V, samples);
   }
   *gather_need = std::min(V, total);
 }
@@ -199,9 +204,11 @@ int sample_core(lgp_ctx* c, const int32_t* seeds, int32_t n_seeds, const int32_t
   launch_mark_ids(c->di, seeds, n_seeds, V, gbits32, n_frontier, c->d_err, s);
   const int32_t* frontier = seeds;
   int64_t cap = n_seeds;
+  const bool want_last = !hot_mode && out->frontier[n_hops] != nullptr;
   for (int h = 0; h < n_hops; ++h) {
-    const bool last = (h + 1 == n_hops);
-    // the last hop's samples only feed the gather set, so they are marked there directly
+    // the last hop's samples only feed the gather set, so they are marked there directly -- unless
+    // the caller wants the last frontier as a list of its own
+    const bool last = (h + 1 == n_hops) && !want_last;
     launch_sample_hop(c->di, tv, frontier, n_frontier + h, cap, fanouts[h], h, rng_seed,
                       hot_mode ? nullptr : out->nbr[h], hot_mode ? nullptr : out->cnt[h], last ? gbits32 : fbits32,
                       hot_mode ? c->topo_hot : nullptr, c->d_err, s);
@@ -397,7 +404,7 @@ int lgp_destroy(lgp_ctx* c) {
   (void)hipDeviceSynchronize();
   free_cache(c);
   void* ptrs[] = {c->row_tab, c->f_remap, c->topo_hot, c->feat_hot, c->fbits, c->gbits, c->chunk_counts,
-                  c->d_err,   c->counters, c->order_t, c->order_f,  c->lists, c->hs_n};
+                  c->d_err,   c->counters, c->order_t, c->order_f,  c->lists, c->hs_n, c->pos_table, c->tile_sums};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   for (int h = 0; h < LGP_MAX_HOPS; ++h)
@@ -424,7 +431,7 @@ int lgp_build_hotness(lgp_ctx* c, const int32_t* train_ids, int64_t n_train, int
   hipStream_t s = static_cast<hipStream_t>(stream);
   LGP_HIP(c, hipSetDevice(c->di.device));
   const int64_t V = c->g.num_vertices;
-  int64_t need[LGP_MAX_HOPS], gather_need;
+  int64_t need[LGP_MAX_HOPS + 1], gather_need;
   worst_case(c, std::min<int64_t>(batch, std::max<int64_t>(n_train, 1)), fanouts, n_hops, need, &gather_need);
   for (int h = 1; h < n_hops; ++h) {
     if (c->hs_cap[h] < need[h]) {
@@ -649,13 +656,15 @@ int lgp_sample_khop(lgp_ctx* c, const int32_t* seeds, int32_t n_seeds, const int
   int st = check_fanouts(c, fanouts, n_hops);
   if (st != LGP_OK) return st;
   if (!out->n_frontier || !out->n_gather) return fail(c, LGP_EINVAL, "out has null count pointers");
-  int64_t need[LGP_MAX_HOPS], gather_need;
+  int64_t need[LGP_MAX_HOPS + 1], gather_need;
   worst_case(c, n_seeds, fanouts, n_hops, need, &gather_need);
   for (int h = 0; h < n_hops; ++h) {
     if (need[h] > 0 && (!out->nbr[h] || !out->cnt[h] || (h > 0 && !out->frontier[h])))
       return fail(c, LGP_EINVAL, "out has a null hop buffer");
     if (out->cap[h] < need[h]) return fail(c, LGP_ECAPACITY, "out->cap[h] is below the worst-case frontier size");
   }
+  if (out->frontier[n_hops] && out->cap[n_hops] < need[n_hops])
+    return fail(c, LGP_ECAPACITY, "out->cap[n_hops] is below the worst-case size of the last frontier");
   if (out->gather_cap < gather_need) return fail(c, LGP_ECAPACITY, "out->gather_cap is below the worst case");
   if (gather_need > 0 && !out->gather_ids) return fail(c, LGP_EINVAL, "out->gather_ids is null");
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -664,6 +673,65 @@ int lgp_sample_khop(lgp_ctx* c, const int32_t* seeds, int32_t n_seeds, const int
   st = sample_core(c, seeds, n_seeds, fanouts, n_hops, rng_seed, out, s);
   prof_end(c, ev, s);
   return st;
+}
+
+int lgp_build_blocks(lgp_ctx* c, const int32_t* seeds, int32_t n_seeds, const int32_t* fanouts, int32_t n_hops,
+                     const lgp_sample_out* sampled, const lgp_blocks_out* out, void* stream) {
+  if (!c) return LGP_EINVAL;
+  if (n_seeds < 0 || (n_seeds > 0 && !seeds) || !sampled || !out) return fail(c, LGP_EINVAL, "seeds / sampled / out");
+  int st = check_fanouts(c, fanouts, n_hops);
+  if (st != LGP_OK) return st;
+  if (!sampled->n_frontier || !sampled->n_gather) return fail(c, LGP_EINVAL, "sampled has null count pointers");
+  int64_t need[LGP_MAX_HOPS + 1], gather_need;
+  worst_case(c, n_seeds, fanouts, n_hops, need, &gather_need);
+  int64_t max_cap = 0;
+  for (int h = 0; h <= n_hops; ++h) {
+    if (h < n_hops && !out->blk_indptr[h]) return fail(c, LGP_EINVAL, "out->blk_indptr[h] is null");
+    if (need[h] == 0) continue;
+    if (sampled->cap[h] < need[h]) return fail(c, LGP_ECAPACITY, "sampled->cap[h] is below the worst case");
+    if (h > 0 && !sampled->frontier[h])
+      return fail(c, LGP_EINVAL, "sampled->frontier[h] is null (the last frontier is needed too)");
+    if (!out->feat_row[h]) return fail(c, LGP_EINVAL, "out->feat_row[h] is null");
+    if (h < n_hops && (!sampled->nbr[h] || !sampled->cnt[h] || !out->blk_indptr[h] || !out->blk_src[h]))
+      return fail(c, LGP_EINVAL, "a hop buffer is null");
+    max_cap = std::max(max_cap, sampled->cap[h]);
+  }
+  if (gather_need > 0 && !sampled->gather_ids) return fail(c, LGP_EINVAL, "sampled->gather_ids is null");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  LGP_HIP(c, hipSetDevice(c->di.device));
+  const int64_t tiles = max_cap / kScanTile + 1;
+  if (!c->pos_table || c->tile_cap < tiles) {
+    LGP_HIP(c, hipStreamSynchronize(s));
+    if (!c->pos_table) LGP_HIP(c, dev_alloc(&c->pos_table, size_t(c->g.num_vertices)));
+    if (c->tile_sums) (void)hipFree(c->tile_sums);
+    c->tile_sums = nullptr;
+    c->tile_cap = 0;
+    LGP_HIP(c, dev_alloc(&c->tile_sums, size_t(tiles)));
+    c->tile_cap = tiles;
+  }
+  const int64_t V = c->g.num_vertices;
+  // rows of every frontier in the extracted feature matrix
+  launch_scatter_pos(c->di, sampled->gather_ids, sampled->n_gather, sampled->gather_cap, c->pos_table, s);
+  for (int h = 0; h <= n_hops; ++h) {
+    if (need[h] == 0) continue;
+    const int32_t* fr = h == 0 ? seeds : sampled->frontier[h];
+    launch_lookup_pos(c->di, fr, sampled->n_frontier + h, sampled->cap[h], c->pos_table, V, out->feat_row[h], s);
+  }
+  // one bipartite block per hop: destinations = frontier h, sources = frontier h + 1
+  for (int h = 0; h < n_hops; ++h) {
+    // an empty frontier still gets its one-entry offset array
+    launch_counts_to_offsets(c->di, sampled->cnt[h], sampled->n_frontier + h, need[h] ? sampled->cap[h] : 0,
+                             c->tile_sums, out->blk_indptr[h], s);
+    if (need[h] == 0) continue;
+    if (need[h + 1] > 0)
+      launch_scatter_pos(c->di, sampled->frontier[h + 1], sampled->n_frontier + h + 1, sampled->cap[h + 1],
+                         c->pos_table, s);
+    launch_relabel(c->di, sampled->nbr[h], out->blk_indptr[h], fanouts[h], sampled->n_frontier + h, sampled->cap[h],
+                   c->pos_table, out->blk_src[h], s);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail_hip(c, e, "graph constructor launch");
+  return LGP_OK;
 }
 
 int lgp_gather_features(lgp_ctx* c, const int32_t* ids, int64_t n_max, const int32_t* n_dev, void* out,

@@ -79,6 +79,21 @@ void launch_gather_rows(const DeviceInfo& di, const void* src, void* dst, int64_
                         const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, bool streaming, hipStream_t s);
 void launch_copy_i32(const int32_t* src, int32_t* dst, int n, hipStream_t s);
 
+// ---- blocks.hip -----------------------------------------------------------
+constexpr int kScanTile = 1024;   // elements per workgroup of the counts -> offsets scan
+// table[ids[j]] = j for j < *n_dev.
+void launch_scatter_pos(const DeviceInfo& di, const int32_t* ids, const int32_t* n_dev, int64_t cap, int32_t* table,
+                        hipStream_t s);
+// out[i] = table[ids[i]] for i < *n_dev (-1 for an id outside [0, V)).
+void launch_lookup_pos(const DeviceInfo& di, const int32_t* ids, const int32_t* n_dev, int64_t cap,
+                       const int32_t* table, int64_t num_vertices, int32_t* out, hipStream_t s);
+// indptr[i] = cnt[0] + ... + cnt[i-1] for i <= *n_dev (64-bit sums); tile_sums holds ceil(cap / kScanTile) entries.
+void launch_counts_to_offsets(const DeviceInfo& di, const int32_t* cnt, const int32_t* n_dev, int64_t cap,
+                              int64_t* tile_sums, int64_t* indptr, hipStream_t s);
+// blk_src[indptr[i] + k] = table[nbr[i, k]] for every valid sample.
+void launch_relabel(const DeviceInfo& di, const int32_t* nbr, const int64_t* indptr, int32_t fanout,
+                    const int32_t* n_dev, int64_t cap, const int32_t* table, int32_t* blk_src, hipStream_t s);
+
 // ---- cache.hip ------------------------------------------------------------
 struct CachePlan {
   int64_t n_topo = 0, topo_edges = 0, n_feat = 0;

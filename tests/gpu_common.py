@@ -53,4 +53,15 @@ def assert_batch_equal(ref: "oracle.Batch", got, tag=""):
         assert fr[h].shape == ref.frontier[h].shape and (fr[h] == ref.frontier[h]).all(), f"{tag} frontier[{h}]"
         assert nbr[h].shape == ref.nbr[h].shape and (nbr[h] == ref.nbr[h]).all(), f"{tag} nbr[{h}]"
         assert (cnt[h] == ref.cnt[h]).all(), f"{tag} cnt[{h}]"
+    if len(fr) == len(ref.frontier):                       # the last frontier was asked for
+        assert fr[-1].shape == ref.frontier[-1].shape and (fr[-1] == ref.frontier[-1]).all(), f"{tag} last frontier"
     assert gids.shape == ref.gather_ids.shape and (gids == ref.gather_ids).all(), f"{tag} gather_ids"
+
+
+def assert_blocks_equal(ref: "oracle.Batch", got, tag=""):
+    indptr, src, rows = got
+    for h in range(len(ref.blk_indptr)):
+        assert indptr[h].shape == ref.blk_indptr[h].shape and (indptr[h] == ref.blk_indptr[h]).all(), f"{tag} indptr[{h}]"
+        assert src[h].shape == ref.blk_src[h].shape and (src[h] == ref.blk_src[h]).all(), f"{tag} blk_src[{h}]"
+    for h in range(len(ref.feat_row)):
+        assert rows[h].shape == ref.feat_row[h].shape and (rows[h] == ref.feat_row[h]).all(), f"{tag} feat_row[{h}]"

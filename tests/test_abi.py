@@ -29,7 +29,8 @@ def test_struct_layouts_match_the_header():
     import paper_2305_16588_amd as lgp
     b = lgp.binding
     assert ctypes.sizeof(b._Graph) == 56 and ctypes.sizeof(b.CachePlan) == 40 and ctypes.sizeof(b.Profile) == 64
-    assert ctypes.sizeof(b._SampleOut) == 4 * 8 * b.MAX_HOPS + 4 * 8
+    assert ctypes.sizeof(b._SampleOut) == 4 * 8 * b.MAX_HOPS + 2 * 8 + 4 * 8
+    assert ctypes.sizeof(b._BlocksOut) == 3 * 8 * b.MAX_HOPS + 8
     hdr = open(os.path.join(ROOT, "include", "legion_prep.h")).read()
     assert f"#define LGP_MAX_HOPS {b.MAX_HOPS}" in hdr and f"#define LGP_MAX_FANOUT {b.MAX_FANOUT}" in hdr
 
@@ -47,6 +48,6 @@ def test_null_arguments_are_rejected_without_a_gpu():
 def test_worst_case_sizes():
     import paper_2305_16588_amd as lgp
     need, g = lgp.worst_case_sizes(2_400_000, 8192, (15, 10, 5))
-    assert need == [8192, 122_880, 1_228_800] and g == 2_400_000
+    assert need == [8192, 122_880, 1_228_800, 2_400_000] and g == 2_400_000
     need, g = lgp.worst_case_sizes(10_000, 1024, (10, 5))
-    assert need == [1024, 10_000] and g == 10_000
+    assert need == [1024, 10_000, 10_000] and g == 10_000

@@ -271,3 +271,24 @@ def test_cslp_algorithm_1(k_g, V, hi, seed):
     assert (acc.cpu().numpy().view(np.uint64) == racc).all()
     assert (order.cpu().numpy() == rorder).all() and (owner.cpu().numpy() == rowner).all()
     assert offsets == roffsets.tolist() and (queues.cpu().numpy() == rqueues).all()
+
+
+@pytest.mark.parametrize("fanouts,n_seeds", [((10, 5), 1024), ((15, 10, 5), 700), ((3,), 1), ((64, 2), 100), ((4, 4), 0),
+                                             ((5, 5, 5, 5), 2048)])
+def test_graph_constructor_blocks(W, fanouts, n_seeds):
+    """Sec. 5's graph constructor: per-hop CSR blocks in local numbering + feature-matrix rows, against the oracle."""
+    from gpu_common import assert_batch_equal, assert_blocks_equal
+    import paper_2305_16588_amd as lgp
+    seeds, seeds_dev = W.tablet[:n_seeds], W.tablet_dev[:n_seeds].contiguous()
+    buf = lgp.SampleBuffers(W.V, max(n_seeds, 1), fanouts, last_frontier=True)
+    W.ctx.sample_khop(seeds_dev, fanouts, 4242, out=buf)
+    blk = W.ctx.build_blocks(seeds_dev, fanouts, buf)
+    ref = W.orc.sample_khop(seeds, fanouts, 4242, blocks=True)
+    assert_batch_equal(ref, buf.to_host(seeds_dev), str(fanouts))
+    assert_blocks_equal(ref, blk.to_host(), str(fanouts))
+    # a second batch through the same buffers (the lookup table is reused without clearing)
+    W.ctx.sample_khop(seeds_dev, fanouts, 4243, out=buf)
+    W.ctx.build_blocks(seeds_dev, fanouts, buf, out=blk)
+    ref = W.orc.sample_khop(seeds, fanouts, 4243, blocks=True)
+    assert_blocks_equal(ref, blk.to_host(), str(fanouts) + " second batch")
+    W.ctx.check()

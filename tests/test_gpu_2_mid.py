@@ -80,3 +80,19 @@ def test_batch_sampling_and_gather(W, b):
     n_hit = W.orc.count_hits(ref.gather_ids, W.qf, W.n_f)
     assert stats.tolist() == [n_hit, n - n_hit] and 0 < n_hit < n
     W.ctx.check()
+
+
+def test_graph_constructor_at_full_size(W):
+    from gpu_common import assert_batch_equal, assert_blocks_equal
+    import paper_2305_16588_amd as lgp
+    spec = W.spec
+    buf = lgp.SampleBuffers(W.V, spec.batch, spec.fanouts, last_frontier=True)
+    blk = lgp.BlockBuffers(buf)
+    for b in (5, 29):
+        seeds, seeds_dev = W.batch(b)
+        W.ctx.sample_khop(seeds_dev, spec.fanouts, 99 + b, out=buf)
+        W.ctx.build_blocks(seeds_dev, spec.fanouts, buf, out=blk)
+        ref = W.orc.sample_khop(seeds, spec.fanouts, 99 + b, blocks=True)
+        assert_batch_equal(ref, buf.to_host(seeds_dev), f"batch {b}")
+        assert_blocks_equal(ref, blk.to_host(), f"batch {b}")
+    W.ctx.check()
