@@ -292,3 +292,75 @@ def test_graph_constructor_blocks(W, fanouts, n_seeds):
     ref = W.orc.sample_khop(seeds, fanouts, 4243, blocks=True)
     assert_blocks_equal(ref, blk.to_host(), str(fanouts) + " second batch")
     W.ctx.check()
+
+
+def test_plan_cache_and_set_hotness():
+    """lgp_plan_cache reports what lgp_build_cache then builds; hotness loaded with lgp_set_hotness ranks the same."""
+    from gpu_common import Workload
+    import paper_2305_16588_amd as lgp
+    Wl = Workload(datagen.TINY)
+    spec = Wl.spec
+    rt, rf, _ = Wl.orc.build_hotness(Wl.tablet, spec.batch, spec.fanouts, spec.base_seed)
+    with pytest.raises(lgp.LegionPrepError) as e:
+        Wl.ctx.plan_cache(1000, 1000)                           # no hotness yet
+    assert e.value.status == -2
+    Wl.ctx.set_hotness(rt, rf)                                  # a saved ranking, no pre-sampling on the GPU
+    topo_b, feat_b = datagen.budgets(spec, Wl.E)
+    p = Wl.ctx.plan_cache(topo_b, feat_b)
+    qt, qf = Wl.orc.rank_by_hotness(rt), Wl.orc.rank_by_hotness(rf)
+    n_t, n_f = Wl.orc.plan_topo(qt, topo_b), Wl.orc.plan_feat(feat_b)
+    assert (p.n_topo, p.n_feat, p.feat_bytes) == (n_t, n_f, n_f * 512)
+    assert p.topo_bytes == int((np.diff(Wl.indptr)[qt[:n_t]].astype(np.int64) * 4 + 8).sum()) <= topo_b
+    b = Wl.ctx.build_cache(topo_b, feat_b)
+    built = (b.n_topo, b.topo_edges, b.topo_bytes, b.n_feat, b.feat_bytes)
+    assert built == (p.n_topo, p.topo_edges, p.topo_bytes, p.n_feat, p.feat_bytes)
+    topo_ids, _, _, feat_ids, _ = Wl.ctx.get_cache()
+    assert (topo_ids == qt[:n_t]).all() and (feat_ids == qf[:n_f]).all()
+    with pytest.raises(lgp.LegionPrepError) as e:
+        Wl.ctx.plan_cache(topo_b, feat_b)                       # planning re-ranks: only before a cache exists
+    assert e.value.status == -2
+
+
+def test_overlap_profiling_and_two_stream_pipelining(W):
+    """The optional modes change scheduling only: same bytes with hit / miss overlap, with event profiling on,
+    and with sampling of the next batch running on a second stream beside the gather of the current one."""
+    from gpu_common import assert_batch_equal
+    import paper_2305_16588_amd as lgp
+    spec = W.spec
+    W.ctx.build_hotness(W.tablet_dev, spec.batch, spec.fanouts, spec.base_seed)
+    W.ctx.build_cache(*datagen.budgets(spec, W.E))
+    refs = [W.orc.sample_khop(W.batch(b)[0], spec.fanouts, 600 + b) for b in range(4)]
+    rows_ref = [W.orc.gather(r.gather_ids) for r in refs]
+    W.ctx.set_overlap(True)
+    W.ctx.set_profiling(True)
+    sA, sB = torch.cuda.Stream(), torch.cuda.Stream()
+    bufs = [lgp.SampleBuffers(W.V, spec.batch, spec.fanouts) for _ in range(2)]
+    outs = [torch.empty((bufs[0].gather_cap, spec.feat_dim), dtype=torch.float32, device="cuda") for _ in range(2)]
+    sampled = [torch.cuda.Event() for _ in range(2)]
+    gathered = [torch.cuda.Event() for _ in range(2)]
+    copied = []
+    torch.cuda.synchronize()
+    for b in range(4):
+        k = b % 2
+        if b >= 2:
+            sA.wait_event(gathered[k])
+        W.ctx.sample_khop(W.batch(b)[1], spec.fanouts, 600 + b, out=bufs[k], stream=sA)
+        sampled[k].record(sA)
+        sB.wait_event(sampled[k])
+        W.ctx.gather_features(bufs[k].gather_ids, n_dev=bufs[k].n_gather, out=outs[k], stream=sB)
+        with torch.cuda.stream(sB):                             # snapshot before the buffer is reused
+            copied.append((outs[k][:refs[b].gather_ids.size].clone(), bufs[k].gather_ids[:refs[b].gather_ids.size].clone(),
+                           bufs[k].n_gather.clone()))
+        gathered[k].record(sB)
+    torch.cuda.synchronize()
+    for b in range(4):
+        rows, gids, n = copied[b]
+        assert int(n.item()) == refs[b].gather_ids.size and (gids.cpu().numpy() == refs[b].gather_ids).all()
+        assert rows.cpu().numpy().tobytes() == rows_ref[b].tobytes()
+    prof = W.ctx.get_profile()
+    assert prof.n_sample == 4 and prof.n_partition == 4 and prof.n_hit == 4 and prof.n_miss == 4
+    assert prof.ms_sample > 0 and prof.ms_hit > 0 and prof.ms_miss > 0
+    W.ctx.set_overlap(False)
+    W.ctx.set_profiling(False)
+    assert W.ctx.get_profile().n_sample == 0                     # reading resets the accumulators
+    W.ctx.check()
