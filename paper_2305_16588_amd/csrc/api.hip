@@ -4,7 +4,6 @@
 
 #include <algorithm>
 #include <cstdio>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -340,7 +339,6 @@ int lgp_create(const lgp_graph* g, int device, lgp_ctx** out) {
   c->di.device = device;
   hipDeviceProp_t prop;
   if (hipGetDeviceProperties(&prop, device) == hipSuccess) c->di.num_cus = prop.multiProcessorCount;
-  if (const char* mb = std::getenv("LGP_MISS_BLOCKS")) c->di.miss_blocks = std::max(1, std::atoi(mb));
   c->g = *g;
   const void* p = nullptr;
   if ((st = device_visible(c, g->indptr, &p, "indptr")) != LGP_OK) return bail(st);
@@ -745,50 +743,62 @@ int lgp_gather_features(lgp_ctx* c, const int32_t* ids, int64_t n_max, const int
   if (vec == 0 || c->row_bytes / vec > 4096) return fail(c, LGP_EUNSUPPORTED, "output alignment too small for this row width");
   hipStream_t s = static_cast<hipStream_t>(stream);
   LGP_HIP(c, hipSetDevice(c->di.device));
-  if (n_max > c->list_cap) {
-    LGP_HIP(c, hipStreamSynchronize(s));
-    LGP_HIP(c, hipStreamSynchronize(c->miss_stream));
-    if (c->lists) (void)hipFree(c->lists);
-    c->lists = nullptr;
-    c->list_cap = 0;
-    LGP_HIP(c, dev_alloc(&c->lists, size_t(n_max) * 4));
-    c->list_cap = n_max;
-  }
   int32_t* counters = stats ? stats : c->counters;
   if (n_max == 0) {
     launch_partition(c->di, ids, 0, nullptr, c->f_remap, c->g.num_vertices, nullptr, nullptr, nullptr, nullptr,
                      counters, c->d_err, s);
     return LGP_OK;
   }
-  int32_t* hit_row = c->lists;
-  int32_t* hit_src = c->lists + c->list_cap;
-  int32_t* miss_row = c->lists + 2 * c->list_cap;
-  int32_t* miss_src = c->lists + 3 * c->list_cap;
-  EvPair ev = prof_begin(c, PK_PARTITION, s);
-  launch_partition(c->di, ids, n_max, n_dev, c->f_remap, c->g.num_vertices, hit_row, hit_src, miss_row, miss_src,
-                   counters, c->d_err, s);
-  prof_end(c, ev, s);
-  // Hits first (HBM -> HBM, short), then misses (PCIe, long).  With overlap enabled the
-  // misses run on a second stream beside the hits and rejoin `s` afterwards.
-  hipStream_t ms = s;
-  if (c->overlap) {
-    ms = c->miss_stream;
-    LGP_HIP(c, hipEventRecord(c->ev_fork, s));
-    LGP_HIP(c, hipStreamWaitEvent(ms, c->ev_fork, 0));
-  }
-  if (c->plan.n_feat > 0) {
+  const int64_t V = c->g.num_vertices;
+  EvPair ev;
+  if (c->plan.n_feat == V) {
+    // every row is cached: no partition, the id list is looked up by the gather itself
+    ev = prof_begin(c, PK_HIT, s);
+    launch_gather_rows(c->di, c->fc, out, c->row_bytes, nullptr, ids, n_max, n_dev, false, s,
+                       DirectIds{c->f_remap, V, counters, 0, c->d_err});
+    prof_end(c, ev, s);
+  } else if (c->plan.n_feat == 0) {
+    // nothing is cached: every id is its own source row in CPU memory
+    ev = prof_begin(c, PK_MISS, s);
+    launch_gather_rows(c->di, c->g.features, out, c->row_bytes, nullptr, ids, n_max, n_dev, true, s,
+                       DirectIds{nullptr, V, counters, 1, c->d_err});
+    prof_end(c, ev, s);
+  } else {
+    if (n_max > c->list_cap) {                     // scratch for the two lists grows on demand
+      LGP_HIP(c, hipStreamSynchronize(s));
+      LGP_HIP(c, hipStreamSynchronize(c->miss_stream));
+      if (c->lists) (void)hipFree(c->lists);
+      c->lists = nullptr;
+      c->list_cap = 0;
+      LGP_HIP(c, dev_alloc(&c->lists, size_t(n_max) * 4));
+      c->list_cap = n_max;
+    }
+    int32_t* hit_row = c->lists;
+    int32_t* hit_src = c->lists + c->list_cap;
+    int32_t* miss_row = c->lists + 2 * c->list_cap;
+    int32_t* miss_src = c->lists + 3 * c->list_cap;
+    ev = prof_begin(c, PK_PARTITION, s);
+    launch_partition(c->di, ids, n_max, n_dev, c->f_remap, V, hit_row, hit_src, miss_row, miss_src, counters,
+                     c->d_err, s);
+    prof_end(c, ev, s);
+    // Hits first (HBM -> HBM, short), then misses (PCIe, long).  With overlap enabled the
+    // misses run on a second stream beside the hits and rejoin `s` afterwards.
+    hipStream_t ms = s;
+    if (c->overlap) {
+      ms = c->miss_stream;
+      LGP_HIP(c, hipEventRecord(c->ev_fork, s));
+      LGP_HIP(c, hipStreamWaitEvent(ms, c->ev_fork, 0));
+    }
     ev = prof_begin(c, PK_HIT, s);
     launch_gather_rows(c->di, c->fc, out, c->row_bytes, hit_row, hit_src, n_max, counters, false, s);
     prof_end(c, ev, s);
-  }
-  if (c->plan.n_feat < c->g.num_vertices) {
     ev = prof_begin(c, PK_MISS, ms);
     launch_gather_rows(c->di, c->g.features, out, c->row_bytes, miss_row, miss_src, n_max, counters + 1, true, ms);
     prof_end(c, ev, ms);
-  }
-  if (c->overlap) {
-    LGP_HIP(c, hipEventRecord(c->ev_join, ms));
-    LGP_HIP(c, hipStreamWaitEvent(s, c->ev_join, 0));
+    if (c->overlap) {
+      LGP_HIP(c, hipEventRecord(c->ev_join, ms));
+      LGP_HIP(c, hipStreamWaitEvent(s, c->ev_join, 0));
+    }
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail_hip(c, e, "gather kernel launch");

@@ -24,7 +24,6 @@ constexpr int64_t kChunkBits = kChunkWords * 64;                     // 65536 ve
 struct DeviceInfo {
   int device = 0;
   int num_cus = 256;
-  int miss_blocks = 512;   // grid of the PCIe row gather
 };
 
 // Row table: one 64-bit entry per vertex, resident in HBM, so that finding a vertex's adjacency
@@ -72,11 +71,22 @@ void launch_compact(const DeviceInfo& di, uint64_t* bits, uint64_t* or_into, int
 void launch_partition(const DeviceInfo& di, const int32_t* ids, int64_t n_max, const int32_t* n_dev,
                       const int32_t* f_remap, int64_t num_vertices, int32_t* hit_row, int32_t* hit_src,
                       int32_t* miss_row, int32_t* miss_src, int32_t* counters, uint32_t* d_err, hipStream_t s);
+// "Direct" launches skip the partition: when every row is cached (or none is) the source-row
+// array is the caller's id list itself.
+struct DirectIds {
+  const int32_t* remap;   // id -> cache slot (everything cached); nullptr = the id is the source row (nothing cached)
+  int64_t num_vertices;   // > 0: entries are vertex ids, validate them; 0: entries are trusted list entries
+  int32_t* stats;         // {n_hit, n_miss} to fill in, or nullptr
+  int32_t stats_slot;     // which of the two gets the row count
+  uint32_t* d_err;
+};
+
 // dst[row[e], :] = src[srcrow[e], :] for e < *n_dev (or n_max if n_dev is null); rows are
 // row_bytes wide; `row` may be null (row = e).  streaming = source is read once over
-// PCIe (non-temporal loads).
+// PCIe (non-temporal loads, one lane group per row).
 void launch_gather_rows(const DeviceInfo& di, const void* src, void* dst, int64_t row_bytes, const int32_t* row,
-                        const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, bool streaming, hipStream_t s);
+                        const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, bool streaming, hipStream_t s,
+                        const DirectIds& dir = DirectIds{nullptr, 0, nullptr, 0, nullptr});
 void launch_copy_i32(const int32_t* src, int32_t* dst, int n, hipStream_t s);
 
 // ---- blocks.hip -----------------------------------------------------------

@@ -85,26 +85,44 @@ __global__ __launch_bounds__(256) void partition_kernel(
   }
 }
 
+__device__ __forceinline__ void direct_stats(const DirectIds& dir, int64_t n) {
+  if (dir.stats && blockIdx.x == 0 && threadIdx.x == 0) {
+    dir.stats[dir.stats_slot] = int32_t(n);
+    dir.stats[1 - dir.stats_slot] = 0;
+  }
+}
+
+// Translate one entry of the source-row array; -1 = skip this row.
+__device__ __forceinline__ int32_t direct_source(const DirectIds& dir, int32_t entry, bool in_range) {
+  if (dir.num_vertices == 0 || !in_range) return in_range ? entry : -1;
+  if (uint32_t(entry) >= uint64_t(dir.num_vertices)) {
+    atomicOr(dir.d_err, ERR_BAD_ID);
+    return -1;
+  }
+  return dir.remap ? dir.remap[entry] : entry;
+}
+
 // ---- cache hits: HBM -> HBM ------------------------------------------------
 // A wavefront takes 64 list entries and walks their rows as one flat run of chunks:
 // all 64 lanes stay busy for any row width and UNROLL loads per lane are in flight
 // before the first store.  Output rows are written once and not read again by this
 // path, so they are stored non-temporally.
-template <typename VecT, int UNROLL>
+template <typename VecT, int UNROLL, bool NT_LOAD>
 __global__ __launch_bounds__(256) void gather_rows_flat_kernel(const VecT* __restrict__ src, VecT* __restrict__ dst,
                                                                uint32_t cpr, uint64_t inv_cpr,
                                                                const int32_t* __restrict__ row,
                                                                const int32_t* __restrict__ srcrow, int64_t n_max,
-                                                               const int32_t* __restrict__ n_dev) {
+                                                               const int32_t* __restrict__ n_dev, DirectIds dir) {
   int64_t n = n_dev ? int64_t(*n_dev) : n_max;
   if (n > n_max) n = n_max;
+  direct_stats(dir, n);
   const int lane = threadIdx.x & 63;
   const int64_t wave = (int64_t(blockIdx.x) * 256 + threadIdx.x) >> 6;
   const int64_t n_waves = int64_t(gridDim.x) * 4;
   for (int64_t e0 = wave * 64; e0 < n; e0 += n_waves * 64) {
     const int64_t e = e0 + lane;
     const int32_t my_row = e < n ? (row ? row[e] : int32_t(e)) : 0;
-    const int32_t my_src = e < n ? srcrow[e] : 0;
+    const int32_t my_src = direct_source(dir, e < n ? srcrow[e] : 0, e < n);
     const uint32_t entries = uint32_t(n - e0 < 64 ? n - e0 : 64);
     const uint32_t total = entries * cpr;          // chunks in this wave's 64 rows
     for (uint32_t f0 = 0; f0 < total; f0 += 64 * UNROLL) {
@@ -119,8 +137,10 @@ __global__ __launch_bounds__(256) void gather_rows_flat_kernel(const VecT* __res
         const uint32_t col = flat - k * cpr;
         const int32_t r = __shfl(my_row, int(k), 64);
         const int32_t sr = __shfl(my_src, int(k), 64);
+        ok[u] = ok[u] && sr >= 0;
         doff[u] = int64_t(r) * cpr + col;
-        if (ok[u]) val[u] = src[int64_t(sr) * cpr + col];
+        if (ok[u])
+          val[u] = NT_LOAD ? __builtin_nontemporal_load(src + int64_t(sr) * cpr + col) : src[int64_t(sr) * cpr + col];
       }
 #pragma unroll
       for (int u = 0; u < UNROLL; ++u)
@@ -139,9 +159,10 @@ template <typename VecT, int G, int UNROLL>
 __global__ __launch_bounds__(256) void gather_rows_group_kernel(const VecT* __restrict__ src, VecT* __restrict__ dst,
                                                                 uint32_t cpr, const int32_t* __restrict__ row,
                                                                 const int32_t* __restrict__ srcrow, int64_t n_max,
-                                                                const int32_t* __restrict__ n_dev) {
+                                                                const int32_t* __restrict__ n_dev, DirectIds dir) {
   int64_t n = n_dev ? int64_t(*n_dev) : n_max;
   if (n > n_max) n = n_max;
+  direct_stats(dir, n);
   const uint32_t sub = threadIdx.x % G;
   const int64_t group = (int64_t(blockIdx.x) * 256 + threadIdx.x) / G;
   const int64_t n_groups = int64_t(gridDim.x) * (256 / G);
@@ -151,7 +172,8 @@ __global__ __launch_bounds__(256) void gather_rows_group_kernel(const VecT* __re
     for (int u = 0; u < UNROLL; ++u) {
       const int64_t e = e0 + u;
       const bool ok = e < n;
-      so[u] = ok ? int64_t(srcrow[e]) * cpr : -1;
+      const int32_t sr = direct_source(dir, ok ? srcrow[e] : 0, ok);
+      so[u] = sr >= 0 ? int64_t(sr) * cpr : -1;
       dof[u] = ok ? int64_t(row ? row[e] : int32_t(e)) * cpr : 0;
     }
     for (uint32_t c0 = 0; c0 < cpr; c0 += G) {
@@ -174,34 +196,42 @@ inline unsigned blocks_for(int64_t work_blocks, int64_t limit) {
 
 template <typename VecT>
 void launch_flat(const DeviceInfo& di, const void* src, void* dst, int64_t row_bytes, const int32_t* row,
-                 const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, hipStream_t s) {
+                 const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, const DirectIds& dir, hipStream_t s) {
   const uint32_t cpr = uint32_t(row_bytes / int64_t(sizeof(VecT)));
   const uint64_t inv = (uint64_t(1) << 32) / cpr + 1;          // exact for flat < 64 * cpr, cpr <= 4096
   const unsigned blocks = blocks_for((n_max + 255) / 256, int64_t(di.num_cus) * 8);
-  hipLaunchKernelGGL((gather_rows_flat_kernel<VecT, 4>), dim3(blocks), dim3(256), 0, s,
-                     static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, inv, row, srcrow, n_max, n_dev);
+  // Rows made of whole 128-byte lines are read once: stream them past L2 (+2.5 % at 512-B and 2-KiB
+  // rows).  Rows that straddle lines share their boundary lines between consecutive load
+  // instructions, and L2 has to merge those (non-temporal loads cost 7 % on 400-B rows).
+  if (row_bytes % 128 == 0)
+    hipLaunchKernelGGL((gather_rows_flat_kernel<VecT, 4, true>), dim3(blocks), dim3(256), 0, s,
+                       static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, inv, row, srcrow, n_max, n_dev, dir);
+  else
+    hipLaunchKernelGGL((gather_rows_flat_kernel<VecT, 4, false>), dim3(blocks), dim3(256), 0, s,
+                       static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, inv, row, srcrow, n_max, n_dev, dir);
 }
 
 template <typename VecT, int G>
 void launch_group_g(const DeviceInfo& di, const void* src, void* dst, uint32_t cpr, const int32_t* row,
-                    const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, hipStream_t s) {
+                    const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, const DirectIds& dir, hipStream_t s) {
   constexpr int U = 4;
-  // PCIe needs far fewer waves than HBM to stay saturated; a small grid leaves the CUs
-  // to the hit gather that runs beside it.
-  const unsigned blocks = blocks_for((n_max + (256 / G) * U - 1) / ((256 / G) * U), int64_t(di.miss_blocks));
+  // PCIe needs far fewer waves than HBM to stay saturated: 2 workgroups per CU already hold
+  // ~8 MB of reads in flight (sequential rows saturate the link with 16 workgroups; random
+  // rows in CPU memory gain until about 512).
+  const unsigned blocks = blocks_for((n_max + (256 / G) * U - 1) / ((256 / G) * U), int64_t(di.num_cus) * 2);
   hipLaunchKernelGGL((gather_rows_group_kernel<VecT, G, U>), dim3(blocks), dim3(256), 0, s,
-                     static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, row, srcrow, n_max, n_dev);
+                     static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, row, srcrow, n_max, n_dev, dir);
 }
 
 template <typename VecT>
 void launch_group(const DeviceInfo& di, const void* src, void* dst, int64_t row_bytes, const int32_t* row,
-                  const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, hipStream_t s) {
+                  const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, const DirectIds& dir, hipStream_t s) {
   const uint32_t cpr = uint32_t(row_bytes / int64_t(sizeof(VecT)));
-  if (cpr <= 4) launch_group_g<VecT, 4>(di, src, dst, cpr, row, srcrow, n_max, n_dev, s);
-  else if (cpr <= 8) launch_group_g<VecT, 8>(di, src, dst, cpr, row, srcrow, n_max, n_dev, s);
-  else if (cpr <= 16) launch_group_g<VecT, 16>(di, src, dst, cpr, row, srcrow, n_max, n_dev, s);
-  else if (cpr <= 32) launch_group_g<VecT, 32>(di, src, dst, cpr, row, srcrow, n_max, n_dev, s);
-  else launch_group_g<VecT, 64>(di, src, dst, cpr, row, srcrow, n_max, n_dev, s);
+  if (cpr <= 4) launch_group_g<VecT, 4>(di, src, dst, cpr, row, srcrow, n_max, n_dev, dir, s);
+  else if (cpr <= 8) launch_group_g<VecT, 8>(di, src, dst, cpr, row, srcrow, n_max, n_dev, dir, s);
+  else if (cpr <= 16) launch_group_g<VecT, 16>(di, src, dst, cpr, row, srcrow, n_max, n_dev, dir, s);
+  else if (cpr <= 32) launch_group_g<VecT, 32>(di, src, dst, cpr, row, srcrow, n_max, n_dev, dir, s);
+  else launch_group_g<VecT, 64>(di, src, dst, cpr, row, srcrow, n_max, n_dev, dir, s);
 }
 
 __global__ void copy_i32_kernel(const int32_t* src, int32_t* dst, int n) {
@@ -223,13 +253,14 @@ void launch_partition(const DeviceInfo& di, const int32_t* ids, int64_t n_max, c
 }
 
 void launch_gather_rows(const DeviceInfo& di, const void* src, void* dst, int64_t row_bytes, const int32_t* row,
-                        const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, bool streaming, hipStream_t s) {
+                        const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, bool streaming, hipStream_t s,
+                        const DirectIds& dir) {
   if (n_max <= 0) return;
   const uintptr_t align = uintptr_t(src) | uintptr_t(dst) | uintptr_t(row_bytes);
 #define LGP_ROWS(VecT)                                                                        \
   do {                                                                                        \
-    if (streaming) launch_group<VecT>(di, src, dst, row_bytes, row, srcrow, n_max, n_dev, s); \
-    else launch_flat<VecT>(di, src, dst, row_bytes, row, srcrow, n_max, n_dev, s);            \
+    if (streaming) launch_group<VecT>(di, src, dst, row_bytes, row, srcrow, n_max, n_dev, dir, s); \
+    else launch_flat<VecT>(di, src, dst, row_bytes, row, srcrow, n_max, n_dev, dir, s);            \
   } while (0)
   if ((align & 15u) == 0) LGP_ROWS(u32x4);
   else if ((align & 7u) == 0) LGP_ROWS(u32x2);
