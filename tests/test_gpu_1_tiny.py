@@ -364,3 +364,42 @@ def test_overlap_profiling_and_two_stream_pipelining(W):
     W.ctx.set_profiling(False)
     assert W.ctx.get_profile().n_sample == 0                     # reading resets the accumulators
     W.ctx.check()
+
+
+def test_hip_graph_capture_and_replay(W):
+    """One batch's whole launch sequence (sampling, dedup, partition, both gathers) captured into a HIP graph and
+    replayed with new seeds in the same buffer: every replay matches the oracle and the eager result.  The path
+    records no memset node; eager work and synchronisations run between replays."""
+    from gpu_common import assert_batch_equal
+    import paper_2305_16588_amd as lgp
+    spec = W.spec
+    W.ctx.build_hotness(W.tablet_dev, spec.batch, spec.fanouts, spec.base_seed)
+    W.ctx.build_cache(*datagen.budgets(spec, W.E))
+    seeds_buf = W.tablet_dev[:spec.batch].clone()
+    buf = lgp.SampleBuffers(W.V, spec.batch, spec.fanouts)
+    rows = torch.empty((buf.gather_cap, spec.feat_dim), dtype=torch.float32, device="cuda")
+    stats = torch.zeros(2, dtype=torch.int32, device="cuda")
+    # warm-up outside capture: grows the library's list scratch (allocation is not capturable)
+    W.ctx.sample_khop(seeds_buf, spec.fanouts, 31, out=buf)
+    W.ctx.gather_features(buf.gather_ids, n_dev=buf.n_gather, out=rows, stats=stats)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        W.ctx.sample_khop(seeds_buf, spec.fanouts, 31, out=buf)
+        W.ctx.gather_features(buf.gather_ids, n_dev=buf.n_gather, out=rows, stats=stats)
+    for b in (3, 0, 7, 3):
+        seeds, seeds_dev = W.batch(b)
+        seeds_buf.copy_(seeds_dev)                                     # eager work between replays
+        rows.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        ref = W.orc.sample_khop(seeds, spec.fanouts, 31)
+        assert_batch_equal(ref, buf.to_host(seeds_buf), f"replay of batch {b}")
+        n = ref.gather_ids.size
+        assert rows[:n].cpu().numpy().tobytes() == W.orc.gather(ref.gather_ids).tobytes()
+        assert int(stats.sum().item()) == n
+        eager = lgp.SampleBuffers(W.V, spec.batch, spec.fanouts)
+        W.ctx.sample_khop(seeds_dev, spec.fanouts, 31, out=eager)       # eager call between replays
+        assert_batch_equal(ref, eager.to_host(seeds_dev), f"eager after replay {b}")
+    W.ctx.check()
