@@ -200,7 +200,6 @@ int sample_core(lgp_ctx* c, const int32_t* seeds, int32_t n_seeds, const int32_t
   int32_t* n_frontier = hot_mode ? c->hs_n : out->n_frontier;
   const TopoView tv = topo_view(c);
 
-  launch_mark_ids(c->di, seeds, n_seeds, V, gbits32, n_frontier, c->d_err, s);
   const int32_t* frontier = seeds;
   int64_t cap = n_seeds;
   const bool want_last = !hot_mode && out->frontier[n_hops] != nullptr;
@@ -210,7 +209,7 @@ int sample_core(lgp_ctx* c, const int32_t* seeds, int32_t n_seeds, const int32_t
     const bool last = (h + 1 == n_hops) && !want_last;
     launch_sample_hop(c->di, tv, frontier, n_frontier + h, cap, fanouts[h], h, rng_seed,
                       hot_mode ? nullptr : out->nbr[h], hot_mode ? nullptr : out->cnt[h], last ? gbits32 : fbits32,
-                      hot_mode ? c->topo_hot : nullptr, c->d_err, s);
+                      h == 0 ? gbits32 : nullptr, hot_mode ? c->topo_hot : nullptr, c->d_err, s);
     if (!last) {
       int32_t* next = hot_mode ? c->hs_frontier[h + 1] : out->frontier[h + 1];
       const int64_t next_cap = hot_mode ? c->hs_cap[h + 1] : out->cap[h + 1];

@@ -49,13 +49,12 @@ struct TopoView {
 // ---- sampler.hip ----------------------------------------------------------
 // Expand frontier[0 .. *n_frontier) with fan-out f at hop `hop`.  Writes nbr / cnt
 // (either may be null), sets the bit of every sampled neighbour in `mark_bits`,
-// adds cnt to topo_hot[v] if topo_hot is given.
-void launch_sample_hop(const DeviceInfo& di, const TopoView& tv, const int32_t* frontier, const int32_t* n_frontier,
+// adds cnt to topo_hot[v] if topo_hot is given.  With self_bits given (first hop) the
+// frontier is the seed list: exactly `cap` ids, *n_frontier is written (= cap) instead of
+// read, and every valid seed's own bit is set in self_bits.
+void launch_sample_hop(const DeviceInfo& di, const TopoView& tv, const int32_t* frontier, int32_t* n_frontier,
                        int64_t cap, int32_t fanout, int32_t hop, uint64_t rng_seed, int32_t* nbr, int32_t* cnt,
-                       uint32_t* mark_bits, uint32_t* topo_hot, uint32_t* d_err, hipStream_t s);
-// Set the bit of every id in ids[0 .. n) and store n to *n_out (if given).
-void launch_mark_ids(const DeviceInfo& di, const int32_t* ids, int32_t n, int64_t num_vertices, uint32_t* bits,
-                     int32_t* n_out, uint32_t* d_err, hipStream_t s);
+                       uint32_t* mark_bits, uint32_t* self_bits, uint32_t* topo_hot, uint32_t* d_err, hipStream_t s);
 
 // ---- compact.hip ----------------------------------------------------------
 // Turn the bitmap `bits` (n_chunks * kChunkWords 64-bit words) into the ascending id

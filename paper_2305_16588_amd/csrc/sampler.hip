@@ -17,11 +17,14 @@ template <typename IdxT, int P>
 __global__ __launch_bounds__(256) void sample_hop_kernel(
     const uint64_t* __restrict__ row_tab, const IdxT* __restrict__ h_indptr, const int32_t* __restrict__ h_indices,
     const int32_t* __restrict__ t_indices, int64_t num_vertices,
-    const int32_t* __restrict__ frontier, const int32_t* __restrict__ n_frontier, int64_t cap, int32_t f, int32_t hop,
+    const int32_t* __restrict__ frontier, int32_t* __restrict__ n_frontier, int64_t cap, int32_t f, int32_t hop,
     uint32_t k0, uint32_t k1, int32_t* __restrict__ nbr, int32_t* __restrict__ cnt, uint32_t* __restrict__ mark_bits,
-    uint32_t* __restrict__ topo_hot, uint32_t* __restrict__ d_err) {
+    uint32_t* __restrict__ self_bits, uint32_t* __restrict__ topo_hot, uint32_t* __restrict__ d_err) {
   constexpr int G = 256 / P;                      // vertices per workgroup pass
-  int64_t n = *n_frontier;
+  // self_bits != nullptr: this is the first hop; the frontier is the caller's seed list of `cap`
+  // ids, whose size is published here and whose members are marked in the gather set.
+  if (self_bits && blockIdx.x == 0 && threadIdx.x == 0) *n_frontier = int32_t(cap);
+  int64_t n = self_bits ? cap : int64_t(*n_frontier);
   if (n > cap) n = cap;                           // never trust a count beyond the buffer
   const int i = threadIdx.x % P;                  // sample slot
   const int gidx = threadIdx.x / P;
@@ -81,6 +84,7 @@ __global__ __launch_bounds__(256) void sample_hop_kernel(
       if (nbr) nbr[g * f + i] = u;
     }
     if (active && i == 0) {
+      if (self_bits && !bad) atomicOr(&self_bits[uint32_t(v) >> 5], 1u << (uint32_t(v) & 31u));
       const int32_t c = d < f ? d : f;
       if (cnt) cnt[g] = c;
       if (topo_hot && c > 0) atomicAdd(&topo_hot[v], uint32_t(c));
@@ -88,22 +92,10 @@ __global__ __launch_bounds__(256) void sample_hop_kernel(
   }
 }
 
-__global__ void mark_ids_kernel(const int32_t* __restrict__ ids, int32_t n, int64_t num_vertices,
-                                uint32_t* __restrict__ bits, int32_t* __restrict__ n_out,
-                                uint32_t* __restrict__ d_err) {
-  const int64_t tid = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
-  if (tid == 0 && n_out) *n_out = n;
-  for (int64_t k = tid; k < n; k += int64_t(gridDim.x) * blockDim.x) {
-    const int32_t u = ids[k];
-    if (uint32_t(u) >= uint64_t(num_vertices)) atomicOr(d_err, ERR_BAD_ID);
-    else atomicOr(&bits[uint32_t(u) >> 5], 1u << (uint32_t(u) & 31u));
-  }
-}
-
 template <typename IdxT, int P>
-void launch_one(const DeviceInfo& di, const TopoView& tv, const int32_t* frontier, const int32_t* n_frontier,
+void launch_one(const DeviceInfo& di, const TopoView& tv, const int32_t* frontier, int32_t* n_frontier,
                 int64_t cap, int32_t f, int32_t hop, uint64_t seed, int32_t* nbr, int32_t* cnt, uint32_t* mark_bits,
-                uint32_t* topo_hot, uint32_t* d_err, hipStream_t s) {
+                uint32_t* self_bits, uint32_t* topo_hot, uint32_t* d_err, hipStream_t s) {
   constexpr int G = 256 / P;
   int64_t blocks = (cap + G - 1) / G;
   const int64_t full = int64_t(di.num_cus) * 8;    // 8 workgroups x 4 waves = 32 waves per CU
@@ -112,17 +104,17 @@ void launch_one(const DeviceInfo& di, const TopoView& tv, const int32_t* frontie
   hipLaunchKernelGGL((sample_hop_kernel<IdxT, P>), dim3(unsigned(blocks)), dim3(256), 0, s,
                      tv.row_tab, static_cast<const IdxT*>(tv.h_indptr), tv.h_indices, tv.t_indices,
                      tv.num_vertices, frontier, n_frontier, cap, f, hop, uint32_t(seed), uint32_t(seed >> 32), nbr,
-                     cnt, mark_bits, topo_hot, d_err);
+                     cnt, mark_bits, self_bits, topo_hot, d_err);
 }
 
 template <typename IdxT>
-void dispatch_p(int P, const DeviceInfo& di, const TopoView& tv, const int32_t* frontier, const int32_t* n_frontier,
+void dispatch_p(int P, const DeviceInfo& di, const TopoView& tv, const int32_t* frontier, int32_t* n_frontier,
                 int64_t cap, int32_t f, int32_t hop, uint64_t seed, int32_t* nbr, int32_t* cnt, uint32_t* mark_bits,
-                uint32_t* topo_hot, uint32_t* d_err, hipStream_t s) {
+                uint32_t* self_bits, uint32_t* topo_hot, uint32_t* d_err, hipStream_t s) {
 #define LGP_CASE(PP)                                                                                            \
   case PP:                                                                                                      \
-    launch_one<IdxT, PP>(di, tv, frontier, n_frontier, cap, f, hop, seed, nbr, cnt, mark_bits, topo_hot, d_err, \
-                         s);                                                                                    \
+    launch_one<IdxT, PP>(di, tv, frontier, n_frontier, cap, f, hop, seed, nbr, cnt, mark_bits, self_bits, topo_hot, \
+                         d_err, s);                                                                              \
     break;
   switch (P) {
     LGP_CASE(1) LGP_CASE(2) LGP_CASE(4) LGP_CASE(8) LGP_CASE(16) LGP_CASE(32) LGP_CASE(64)
@@ -132,25 +124,17 @@ void dispatch_p(int P, const DeviceInfo& di, const TopoView& tv, const int32_t* 
 
 }  // namespace
 
-void launch_sample_hop(const DeviceInfo& di, const TopoView& tv, const int32_t* frontier, const int32_t* n_frontier,
+void launch_sample_hop(const DeviceInfo& di, const TopoView& tv, const int32_t* frontier, int32_t* n_frontier,
                        int64_t cap, int32_t fanout, int32_t hop, uint64_t rng_seed, int32_t* nbr, int32_t* cnt,
-                       uint32_t* mark_bits, uint32_t* topo_hot, uint32_t* d_err, hipStream_t s) {
+                       uint32_t* mark_bits, uint32_t* self_bits, uint32_t* topo_hot, uint32_t* d_err, hipStream_t s) {
   int P = 1;
   while (P < fanout) P <<= 1;
   if (tv.indptr_bytes == 8)
-    dispatch_p<int64_t>(P, di, tv, frontier, n_frontier, cap, fanout, hop, rng_seed, nbr, cnt, mark_bits, topo_hot,
-                        d_err, s);
+    dispatch_p<int64_t>(P, di, tv, frontier, n_frontier, cap, fanout, hop, rng_seed, nbr, cnt, mark_bits, self_bits,
+                        topo_hot, d_err, s);
   else
-    dispatch_p<int32_t>(P, di, tv, frontier, n_frontier, cap, fanout, hop, rng_seed, nbr, cnt, mark_bits, topo_hot,
-                        d_err, s);
-}
-
-void launch_mark_ids(const DeviceInfo& di, const int32_t* ids, int32_t n, int64_t num_vertices, uint32_t* bits,
-                     int32_t* n_out, uint32_t* d_err, hipStream_t s) {
-  int blocks = (n + 255) / 256;
-  if (blocks > di.num_cus * 4) blocks = di.num_cus * 4;
-  if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL(mark_ids_kernel, dim3(blocks), dim3(256), 0, s, ids, n, num_vertices, bits, n_out, d_err);
+    dispatch_p<int32_t>(P, di, tv, frontier, n_frontier, cap, fanout, hop, rng_seed, nbr, cnt, mark_bits, self_bits,
+                        topo_hot, d_err, s);
 }
 
 }  // namespace lgp
