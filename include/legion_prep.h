@@ -125,6 +125,14 @@ int lgp_host_free(void* ptr);
 int lgp_create(const lgp_graph* g, int device, lgp_ctx** out);
 int lgp_destroy(lgp_ctx* ctx);
 
+/* Batch generator (Sec. 5, operator 1: "shuffles the local training vertices to generate
+ * seeds for mini batches").  out[j] = in[pi(j)] where pi orders the positions 0 .. n-1 by the
+ * 64-bit Philox4x32-10 draw keyed (seed, position, epoch, 0), ascending, ties by position:
+ * a reproducible permutation per epoch.  in / out are [device], n ids each, and must not
+ * overlap.  Needs no context; runs on `device`; allocates sort scratch; synchronous. */
+int lgp_shuffle_tablet(int device, const int32_t* in, int32_t* out, int64_t n, uint64_t seed, uint32_t epoch,
+                       void* stream);
+
 /* Pre-sampling (Sec. 4.2.2, step S1).  The tablet train_ids [device, n_train ids,
  * already in epoch order] is cut into consecutive mini-batches of `batch` seeds (the
  * last may be short); batch b is sampled with rng seed base_seed + b; column ids come

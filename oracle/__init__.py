@@ -81,6 +81,8 @@ def _load():
         L.orc_count_hits.restype = i64
         L.orc_search_cache_plan.argtypes = [gp, vp, vp, vp, vp, i64, u64, u64, C.c_uint32, i32, vp]
         L.orc_search_cache_plan.restype = i32
+        L.orc_shuffle_tablet.argtypes = [vp, vp, i64, u64, C.c_uint32]
+        L.orc_shuffle_tablet.restype = None
         L.orc_cslp.argtypes = [i32, i64, vp, vp, vp, vp, vp, vp]
         L.orc_cslp.restype = None
         _lib = L
@@ -112,6 +114,14 @@ def philox4x32_10(ctr, key) -> np.ndarray:
 
 def draw64(rng_seed: int, v: int, hop: int, slot: int) -> int:
     return int(_load().orc_draw64(rng_seed & (2**64 - 1), v, hop, slot))
+
+
+def shuffle_tablet(train_ids: np.ndarray, seed: int, epoch: int) -> np.ndarray:
+    """Batch generator: the tablet in the order of epoch `epoch`."""
+    train_ids = np.ascontiguousarray(train_ids, dtype=np.int32)
+    out = np.empty_like(train_ids)
+    _load().orc_shuffle_tablet(_p(train_ids), _p(out), train_ids.size, seed & (2**64 - 1), epoch)
+    return out
 
 
 def cslp(hot: np.ndarray):

@@ -209,6 +209,18 @@ int64_t orc_batch_gather_size(const void* h) { return (int64_t) static_cast<cons
 const int32_t* orc_batch_gather_ids(const void* h) { return static_cast<const Batch*>(h)->gather_ids.data(); }
 void orc_batch_free(void* h) { delete static_cast<Batch*>(h); }
 
+// --- batch generator (Sec. 5, operator 1) -------------------------------------
+// "Shuffles the local training vertices to generate seeds for mini batches."  The paper names
+// no shuffle; here position i of the tablet gets the 64-bit key draw64(seed, i, epoch, 0) and
+// the tablet is reordered by ascending key (ties by position), so every epoch has its own
+// reproducible order.
+void orc_shuffle_tablet(const int32_t* in, int32_t* out, int64_t n, uint64_t seed, uint32_t epoch) {
+  std::vector<std::pair<uint64_t, int64_t>> keyed(n);
+  for (int64_t i = 0; i < n; ++i) keyed[i] = {draw64(seed, i, static_cast<int32_t>(epoch), 0), i};
+  std::sort(keyed.begin(), keyed.end());
+  for (int64_t i = 0; i < n; ++i) out[i] = in[keyed[i].second];
+}
+
 // --- graph constructor (Sec. 5, operator 4) ----------------------------------
 // The paper only says the constructor "generates the subgraph based on the sampled
 // results".  Reading used here: hop h becomes a bipartite block in CSR form whose

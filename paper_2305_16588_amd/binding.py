@@ -58,7 +58,7 @@ class Profile(C.Structure):
                 ("ms_miss", C.c_double)]
 
 
-EXPORTS = ["lgp_host_alloc", "lgp_host_free", "lgp_create", "lgp_destroy", "lgp_build_hotness", "lgp_get_hotness",
+EXPORTS = ["lgp_host_alloc", "lgp_host_free", "lgp_shuffle_tablet", "lgp_create", "lgp_destroy", "lgp_build_hotness", "lgp_get_hotness",
            "lgp_set_hotness", "lgp_plan_cache", "lgp_search_cache_plan", "lgp_cslp", "lgp_build_cache", "lgp_get_cache_plan", "lgp_get_cache",
            "lgp_sample_khop", "lgp_build_blocks", "lgp_gather_features", "lgp_set_overlap", "lgp_check", "lgp_set_profiling", "lgp_get_profile",
            "lgp_strerror", "lgp_last_error"]
@@ -85,6 +85,7 @@ def load_library():
     L.lgp_set_hotness.argtypes = [vp, vp, vp]
     L.lgp_plan_cache.argtypes = [vp, u64, u64, C.POINTER(CachePlan), vp]
     L.lgp_search_cache_plan.argtypes = [vp, u64, u64, C.c_uint32, i32, vp, vp, vp]
+    L.lgp_shuffle_tablet.argtypes = [C.c_int, vp, vp, i64, u64, C.c_uint32, vp]
     L.lgp_cslp.argtypes = [C.c_int, i32, i64, vp, vp, vp, vp, vp, vp, vp]
     L.lgp_build_cache.argtypes = [vp, u64, u64, vp]
     L.lgp_get_cache_plan.argtypes = [vp, C.POINTER(CachePlan)]
@@ -142,6 +143,18 @@ def worst_case_sizes(num_vertices: int, n_seeds: int, fanouts):
         total += samples
         need.append(min(num_vertices, samples))
     return need, min(num_vertices, total)
+
+
+def shuffle_tablet(train_ids: torch.Tensor, seed: int, epoch: int, stream=None) -> torch.Tensor:
+    """Batch generator: the tablet (int32 CUDA tensor) in the order of epoch `epoch`."""
+    L = load_library()
+    assert train_ids.is_cuda and train_ids.dtype == torch.int32 and train_ids.is_contiguous()
+    out = torch.empty_like(train_ids)
+    st = L.lgp_shuffle_tablet(train_ids.device.index or 0, train_ids.data_ptr(), out.data_ptr(), train_ids.numel(),
+                              seed & (2**64 - 1), epoch, _stream_ptr(stream))
+    if st != 0:
+        raise LegionPrepError(st, L.lgp_strerror(st).decode())
+    return out
 
 
 def cslp(hot: torch.Tensor, stream=None):

@@ -540,6 +540,28 @@ int lgp_search_cache_plan(lgp_ctx* c, uint64_t total_budget, uint64_t n_tsum, ui
   return LGP_OK;
 }
 
+int lgp_shuffle_tablet(int device, const int32_t* in, int32_t* out, int64_t n, uint64_t seed, uint32_t epoch,
+                       void* stream) {
+  if (n < 0 || (n > 0 && (!in || !out))) return LGP_EINVAL;
+  if (n >= (int64_t(1) << 31)) return LGP_EUNSUPPORTED;   // positions are 32-bit counter words
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess || device < 0 || device >= n_dev || hipSetDevice(device) != hipSuccess) {
+    (void)hipGetLastError();
+    return LGP_EINVAL;
+  }
+  if (n == 0) return LGP_OK;
+  DeviceInfo di;
+  di.device = device;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, device) == hipSuccess) di.num_cus = prop.multiProcessorCount;
+  hipError_t e = shuffle_by_key(di, in, out, n, seed, epoch, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return e == hipErrorOutOfMemory ? LGP_ENOMEM : LGP_EHIP;
+  }
+  return LGP_OK;
+}
+
 int lgp_cslp(int device, int32_t k_g, int64_t num_vertices, const uint32_t* hot, uint64_t* acc, int32_t* order,
              int32_t* owner, int32_t* queues, int64_t* queue_offsets, void* stream) {
   if (k_g < 1 || num_vertices < 1 || !hot || !acc || !order || !owner || !queues || !queue_offsets) return LGP_EINVAL;

@@ -10,6 +10,8 @@
 
 #include <rocprim/rocprim.hpp>
 
+#include "philox_dev.hpp"
+
 namespace lgp {
 namespace {
 
@@ -76,6 +78,11 @@ __global__ __launch_bounds__(1024) void alpha_search_kernel(
       if (less128(U128{key_hi[k], key_lo[k]}, U128{key_hi[b], key_lo[b]})) b = k;
     *best = b;
   }
+}
+
+__global__ void shuffle_keys_kernel(uint64_t* __restrict__ keys, int64_t n, uint32_t k0, uint32_t k1, uint32_t epoch) {
+  for (int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < n; i += int64_t(gridDim.x) * blockDim.x)
+    keys[i] = philox_draw64(k0, k1, uint32_t(i), epoch, 0u);
 }
 
 // Algorithm 1 step 1 + the arg-max of step 3: one thread per vertex walks its column.
@@ -263,6 +270,27 @@ void launch_alpha_search(const uint64_t* cost_scan, const uint64_t* hot_t_scan, 
                          hipStream_t s) {
   hipLaunchKernelGGL(alpha_search_kernel, dim3(1), dim3(1024), 0, s, cost_scan, hot_t_scan, hot_f_scan, num_vertices,
                      row_bytes, m_topo, total_budget, n_tsum, per_row, n_alpha, points, best);
+}
+
+hipError_t shuffle_by_key(const DeviceInfo& di, const int32_t* in, int32_t* out, int64_t n, uint64_t seed,
+                          uint32_t epoch, hipStream_t s) {
+  uint64_t *keys = nullptr, *keys_out = nullptr;
+  void* temp = nullptr;
+  size_t temp_bytes = 0;
+  hipError_t e = hipMalloc(&keys, sizeof(uint64_t) * size_t(n));
+  if (e == hipSuccess) e = hipMalloc(&keys_out, sizeof(uint64_t) * size_t(n));
+  if (e == hipSuccess) {
+    hipLaunchKernelGGL(shuffle_keys_kernel, dim3(grid_for(di, n)), dim3(256), 0, s, keys, n, uint32_t(seed),
+                       uint32_t(seed >> 32), epoch);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) e = rocprim::radix_sort_pairs(nullptr, temp_bytes, keys, keys_out, in, out, size_t(n), 0, 64, s);
+  if (e == hipSuccess) e = hipMalloc(&temp, temp_bytes + 16);
+  if (e == hipSuccess) e = rocprim::radix_sort_pairs(temp, temp_bytes, keys, keys_out, in, out, size_t(n), 0, 64, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  for (void* p : {static_cast<void*>(keys), static_cast<void*>(keys_out), temp})
+    if (p) (void)hipFree(p);
+  return e;
 }
 
 hipError_t cslp_rank(const DeviceInfo& di, int32_t k_g, int64_t num_vertices, const uint32_t* hot, uint64_t* acc,

@@ -138,6 +138,9 @@ void launch_alpha_search(const uint64_t* cost_scan, const uint64_t* hot_t_scan, 
                          uint64_t n_tsum, uint64_t per_row, int32_t n_alpha, lgp_plan_point* points, int32_t* best,
                          hipStream_t s);
 void launch_fill_i32(const DeviceInfo& di, int32_t* p, int64_t n, int32_t value, hipStream_t s);
+// out = in reordered by ascending Philox key of the position (one permutation per epoch).  Synchronises `s`.
+hipError_t shuffle_by_key(const DeviceInfo& di, const int32_t* in, int32_t* out, int64_t n, uint64_t seed,
+                          uint32_t epoch, hipStream_t s);
 // Algorithm 1 for k_g hotness rows: column sums, ranking, arg-max owner, per-GPU queues.  counts
 // (device uint64[k_g]) receives the queue lengths.  Synchronises `s`.
 hipError_t cslp_rank(const DeviceInfo& di, int32_t k_g, int64_t num_vertices, const uint32_t* hot, uint64_t* acc,

@@ -403,3 +403,12 @@ def test_hip_graph_capture_and_replay(W):
         W.ctx.sample_khop(seeds_dev, spec.fanouts, 31, out=eager)       # eager call between replays
         assert_batch_equal(ref, eager.to_host(seeds_dev), f"eager after replay {b}")
     W.ctx.check()
+
+
+@pytest.mark.parametrize("n,seed,epoch", [(0, 1, 0), (1, 2, 0), (10_000, 2**40 + 17, 3), (1_000_003, 5, 2**31)])
+def test_batch_generator_shuffle(n, seed, epoch):
+    import oracle
+    import paper_2305_16588_amd as lgp
+    ids = np.random.default_rng(n).integers(0, 2**31 - 1, size=n).astype(np.int32)
+    out = lgp.shuffle_tablet(torch.from_numpy(ids).cuda(), seed, epoch)
+    assert (out.cpu().numpy() == oracle.shuffle_tablet(ids, seed, epoch)).all()
