@@ -226,8 +226,11 @@ int lgp_build_blocks(lgp_ctx* ctx, const int32_t* seeds, int32_t n_seeds, const 
  * order, duplicates allowed); n = *n_dev if n_dev [device int32] is given, else n_max;
  * out is [device] with room for n_max rows.  Ids are split into cache hits (rows read
  * from the HBM feature cache) and misses (rows read in place from CPU memory over
- * PCIe); stats [device int32[2], may be NULL] receives {n_hit, n_miss}.  Scratch for
- * the two lists grows on demand (a growth step allocates and synchronises). */
+ * PCIe); stats [device int32[2], may be NULL] receives {n_hit, n_miss} (unspecified if
+ * lgp_check then reports an invalid id).  When every row is cached, or none, the split is
+ * skipped and one gather looks the ids up itself.  Otherwise scratch for the two lists
+ * grows on demand (a growth step allocates and synchronises), so call once with the
+ * largest n_max before capturing the call into a HIP graph. */
 int lgp_gather_features(lgp_ctx* ctx, const int32_t* ids, int64_t n_max, const int32_t* n_dev, void* out,
                         int32_t* stats, void* stream);
 

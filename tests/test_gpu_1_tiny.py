@@ -412,3 +412,24 @@ def test_batch_generator_shuffle(n, seed, epoch):
     ids = np.random.default_rng(n).integers(0, 2**31 - 1, size=n).astype(np.int32)
     out = lgp.shuffle_tablet(torch.from_numpy(ids).cuda(), seed, epoch)
     assert (out.cpu().numpy() == oracle.shuffle_tablet(ids, seed, epoch)).all()
+
+
+def test_duplicate_seeds_and_presampling_through_an_existing_cache(W):
+    """Seeds given twice are expanded twice (identical rows) and merge at the first dedup; pre-sampling after a
+    cache was built reads through that cache and still counts exactly what the oracle counts."""
+    from gpu_common import assert_batch_equal
+    spec = W.spec
+    W.ctx.build_hotness(W.tablet_dev, spec.batch, spec.fanouts, spec.base_seed)
+    W.ctx.build_cache(*datagen.budgets(spec, W.E))
+    seeds = np.concatenate([W.tablet[:50], W.tablet[:50], W.tablet[40:90]]).astype(np.int32)
+    dev = torch.from_numpy(seeds).cuda()
+    buf = W.ctx.sample_khop(dev, (10, 5), 8)
+    ref = W.orc.sample_khop(seeds, (10, 5), 8)
+    assert_batch_equal(ref, buf.to_host(dev), "duplicate seeds")
+    assert (ref.nbr[0][:50] == ref.nbr[0][50:100]).all()
+    tab = torch.from_numpy(np.concatenate([seeds, W.tablet[:3000]])).cuda()
+    W.ctx.build_hotness(tab, 700, spec.fanouts, 77)              # cache from above is in place
+    topo, feat = W.ctx.get_hotness()
+    rt, rf, _ = W.orc.build_hotness(tab.cpu().numpy(), 700, spec.fanouts, 77)
+    assert (topo == rt).all() and (feat == rf).all()
+    W.ctx.check()
