@@ -433,3 +433,45 @@ def test_duplicate_seeds_and_presampling_through_an_existing_cache(W):
     rt, rf, _ = W.orc.build_hotness(tab.cpu().numpy(), 700, spec.fanouts, 77)
     assert (topo == rt).all() and (feat == rf).all()
     W.ctx.check()
+
+
+@pytest.mark.parametrize("dim,dtype", [(1, "float16"), (2, "float16"), (3, "float32"), (6, "float32"), (4, "float32"),
+                                       (20, "float32"), (36, "float32"), (100, "float16"), (256, "float32"),
+                                       (1024, "float32"), (8192, "float16"), (16384, "float32")])
+def test_gather_row_widths(dim, dtype):
+    """Every chunk width (2 / 4 / 8 / 16 bytes) and lane-group size of the two gather kernels, from 2-byte rows to
+    the 64-KiB limit, through the partitioned path and both direct paths (nothing cached / everything cached)."""
+    import oracle
+    import paper_2305_16588_amd as lgp
+    V = 3000
+    indptr, indices = datagen.tiny_graph(V, 4.0, 3)
+    rng = np.random.default_rng(dim)
+    npdt = np.float16 if dtype == "float16" else np.float32
+    feats = lgp.pinned_empty((V, dim), npdt)
+    feats[...] = rng.standard_normal((V, dim)).astype(npdt)
+    p_indptr, p_indices = lgp.pinned_copy(indptr), lgp.pinned_copy(indices)
+    ctx = lgp.Context(p_indptr, p_indices, feats)
+    orc = oracle.Oracle(indptr, indices, feats)
+    row_bytes = dim * np.dtype(npdt).itemsize
+    ids = rng.integers(0, V, size=2500).astype(np.int32)
+    dev = torch.from_numpy(ids).cuda()
+    ref = orc.gather(ids).tobytes()
+    ctx.set_hotness(rng.integers(0, 9, V).astype(np.uint32), rng.integers(0, 9, V).astype(np.uint32))
+    for n_cached in (0, 1200, V):
+        plan = ctx.build_cache(0, n_cached * row_bytes)
+        assert plan.n_feat == n_cached
+        stats = torch.zeros(2, dtype=torch.int32, device="cuda")
+        rows = ctx.gather_features(dev, stats=stats)
+        assert rows.cpu().numpy().tobytes() == ref, f"{n_cached} rows cached"
+        assert int(stats.sum().item()) == ids.size
+    ctx.check()
+    ctx.close()
+
+
+def test_row_wider_than_the_limit_is_refused():
+    import paper_2305_16588_amd as lgp
+    indptr, indices = datagen.tiny_graph(10, 2.0, 1)
+    feats = lgp.pinned_empty((10, 16385), np.float32)           # 65 540-byte rows: 4-byte chunks, 16 385 of them
+    with pytest.raises(lgp.LegionPrepError) as e:
+        lgp.Context(lgp.pinned_copy(indptr), lgp.pinned_copy(indices), feats)
+    assert e.value.status == -4
