@@ -154,8 +154,9 @@ __global__ __launch_bounds__(256) void gather_rows_flat_kernel(const VecT* __res
 // a line requested by two different load instructions crosses the link twice.  Here a
 // group of G >= chunks-per-row lanes owns a whole row, so one instruction requests each
 // line of the row exactly once; UNROLL rows per group are in flight before the first
-// store.  Rows wider than 64 chunks are walked in 64-chunk pieces.
-template <typename VecT, int G, int UNROLL>
+// store.  Rows wider than 64 chunks are walked in 64-chunk pieces.  HBM_SOURCE selects the
+// variant used for cache hits on rows that straddle lines (cached loads, streaming stores).
+template <typename VecT, int G, int UNROLL, bool HBM_SOURCE>
 __global__ __launch_bounds__(256) void gather_rows_group_kernel(const VecT* __restrict__ src, VecT* __restrict__ dst,
                                                                 uint32_t cpr, const int32_t* __restrict__ row,
                                                                 const int32_t* __restrict__ srcrow, int64_t n_max,
@@ -181,10 +182,13 @@ __global__ __launch_bounds__(256) void gather_rows_group_kernel(const VecT* __re
       VecT val[UNROLL];
 #pragma unroll
       for (int u = 0; u < UNROLL; ++u)
-        if (so[u] >= 0 && col < cpr) val[u] = __builtin_nontemporal_load(src + so[u] + col);
+        if (so[u] >= 0 && col < cpr) val[u] = HBM_SOURCE ? src[so[u] + col] : __builtin_nontemporal_load(src + so[u] + col);
 #pragma unroll
       for (int u = 0; u < UNROLL; ++u)
-        if (so[u] >= 0 && col < cpr) dst[dof[u] + col] = val[u];
+        if (so[u] >= 0 && col < cpr) {
+          if (HBM_SOURCE) __builtin_nontemporal_store(val[u], dst + dof[u] + col);
+          else dst[dof[u] + col] = val[u];
+        }
     }
   }
 }
@@ -219,8 +223,29 @@ void launch_group_g(const DeviceInfo& di, const void* src, void* dst, uint32_t c
   // ~8 MB of reads in flight (sequential rows saturate the link with 16 workgroups; random
   // rows in CPU memory gain until about 512).
   const unsigned blocks = blocks_for((n_max + (256 / G) * U - 1) / ((256 / G) * U), int64_t(di.num_cus) * 2);
-  hipLaunchKernelGGL((gather_rows_group_kernel<VecT, G, U>), dim3(blocks), dim3(256), 0, s,
+  hipLaunchKernelGGL((gather_rows_group_kernel<VecT, G, U, false>), dim3(blocks), dim3(256), 0, s,
                      static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, row, srcrow, n_max, n_dev, dir);
+}
+
+// Cache hits whose rows straddle 128-byte lines (e.g. 400-byte rows): one lane group per row, one
+// row per group in flight.  Every line of a row is then requested by a single load instruction,
+// which beats the flat walk by ~5 % on such rows; rows made of whole lines stay with the flat kernel.
+template <typename VecT, int G>
+void launch_group_hbm_g(const DeviceInfo& di, const void* src, void* dst, uint32_t cpr, const int32_t* row,
+                        const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, const DirectIds& dir,
+                        hipStream_t s) {
+  const unsigned blocks = blocks_for((n_max + 256 / G - 1) / (256 / G), int64_t(di.num_cus) * 8);
+  hipLaunchKernelGGL((gather_rows_group_kernel<VecT, G, 1, true>), dim3(blocks), dim3(256), 0, s,
+                     static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, row, srcrow, n_max, n_dev, dir);
+}
+
+template <typename VecT>
+void launch_group_hbm(const DeviceInfo& di, const void* src, void* dst, uint32_t cpr, const int32_t* row,
+                      const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, const DirectIds& dir, hipStream_t s) {
+  if (cpr <= 4) launch_group_hbm_g<VecT, 4>(di, src, dst, cpr, row, srcrow, n_max, n_dev, dir, s);
+  else if (cpr <= 8) launch_group_hbm_g<VecT, 8>(di, src, dst, cpr, row, srcrow, n_max, n_dev, dir, s);
+  else if (cpr <= 16) launch_group_hbm_g<VecT, 16>(di, src, dst, cpr, row, srcrow, n_max, n_dev, dir, s);
+  else launch_group_hbm_g<VecT, 32>(di, src, dst, cpr, row, srcrow, n_max, n_dev, dir, s);
 }
 
 template <typename VecT>
@@ -260,6 +285,8 @@ void launch_gather_rows(const DeviceInfo& di, const void* src, void* dst, int64_
 #define LGP_ROWS(VecT)                                                                        \
   do {                                                                                        \
     if (streaming) launch_group<VecT>(di, src, dst, row_bytes, row, srcrow, n_max, n_dev, dir, s); \
+    else if (row_bytes % 128 != 0 && row_bytes / sizeof(VecT) <= 32)                               \
+      launch_group_hbm<VecT>(di, src, dst, uint32_t(row_bytes / sizeof(VecT)), row, srcrow, n_max, n_dev, dir, s); \
     else launch_flat<VecT>(di, src, dst, row_bytes, row, srcrow, n_max, n_dev, dir, s);            \
   } while (0)
   if ((align & 15u) == 0) LGP_ROWS(u32x4);
