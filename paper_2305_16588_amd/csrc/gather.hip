@@ -11,6 +11,8 @@
 // need to sit in LDS because a chunk is loaded and stored by the same lane.
 #include "common.hpp"
 
+#include <algorithm>
+
 namespace lgp {
 namespace {
 
@@ -219,10 +221,11 @@ template <typename VecT, int G>
 void launch_group_g(const DeviceInfo& di, const void* src, void* dst, uint32_t cpr, const int32_t* row,
                     const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, const DirectIds& dir, hipStream_t s) {
   constexpr int U = 4;
-  // PCIe needs far fewer waves than HBM to stay saturated: 2 workgroups per CU already hold
-  // ~8 MB of reads in flight (sequential rows saturate the link with 16 workgroups; random
-  // rows in CPU memory gain until about 512).
-  const unsigned blocks = blocks_for((n_max + (256 / G) * U - 1) / ((256 / G) * U), int64_t(di.num_cus) * 2);
+  // PCIe needs far fewer waves than HBM to stay saturated (bandwidth x latency is ~150 KB): one
+  // workgroup per four CUs holds ~1 MB of reads in flight, and measured rates FALL with wider grids
+  // (400-B rows 44.9 -> 44.0 GB/s, 2-KiB rows 57.5 -> 55.7 GB/s from 64 to 512 workgroups), because the
+  // excess requests only queue up in front of the link.
+  const unsigned blocks = blocks_for((n_max + (256 / G) * U - 1) / ((256 / G) * U), std::max(1, di.num_cus / 4));
   hipLaunchKernelGGL((gather_rows_group_kernel<VecT, G, U, false>), dim3(blocks), dim3(256), 0, s,
                      static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, row, srcrow, n_max, n_dev, dir);
 }
