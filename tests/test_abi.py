@@ -51,3 +51,35 @@ def test_worst_case_sizes():
     assert need == [8192, 122_880, 1_228_800, 2_400_000] and g == 2_400_000
     need, g = lgp.worst_case_sizes(10_000, 1024, (10, 5))
     assert need == [1024, 10_000, 10_000] and g == 10_000
+
+
+def test_calls_fail_cleanly_when_no_gpu_is_present():
+    """On a machine without a GPU every entry point that needs one returns an error code; nothing crashes
+    and nothing falls back to the CPU."""
+    import numpy as np
+    import torch
+    import paper_2305_16588_amd as lgp
+    if torch.cuda.is_available():
+        import pytest
+        pytest.skip("a GPU is present")
+    lib = lgp.load_library()
+    b = lgp.binding
+    indptr = np.array([0, 1, 2], dtype=np.int32)
+    indices = np.array([1, 0], dtype=np.int32)
+    g = b._Graph()
+    g.num_vertices, g.num_edges = 2, 2
+    g.indptr, g.indptr_bytes, g.indices = indptr.ctypes.data, 4, indices.ctypes.data
+    h = ctypes.c_void_p()
+    assert lib.lgp_create(ctypes.byref(g), 0, ctypes.byref(h)) < 0 and not h.value
+    p = ctypes.c_void_p(123)
+    assert lib.lgp_host_alloc(1024, ctypes.byref(p)) == -6 and not p.value
+    offs = (ctypes.c_int64 * 2)()
+    dummy = ctypes.c_void_p(8)
+    assert lib.lgp_cslp(0, 1, 2, dummy, dummy, dummy, dummy, dummy, ctypes.addressof(offs), None) == -1
+    assert lib.lgp_shuffle_tablet(0, dummy, dummy, 2, 1, 0, None) == -1
+    g.indptr_bytes = 3
+    assert lib.lgp_create(ctypes.byref(g), 0, ctypes.byref(h)) == -1          # bad offset width
+    g.indptr_bytes, g.num_vertices = 4, 2**31
+    assert lib.lgp_create(ctypes.byref(g), 0, ctypes.byref(h)) == -4          # too many vertices for int32 ids
+    with __import__("pytest").raises(lgp.LegionPrepError):
+        lgp.pinned_empty(16, np.int32)
