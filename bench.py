@@ -39,6 +39,9 @@ def main() -> int:
     ap.add_argument("--workload", default="mid", help="tiny | mid | wide | large | share (optionally name@scale)")
     ap.add_argument("--feat-frac", type=float, default=None, help="override the feature-cache ratio")
     ap.add_argument("--topo-frac", type=float, default=None, help="override the topology-cache ratio")
+    ap.add_argument("--cache-bytes", type=int, default=0,
+                    help="one total cache budget B instead of the two ratios; split by --alpha, or by the cost model")
+    ap.add_argument("--alpha", type=float, default=None, help="topology share of --cache-bytes (default: cost-model search)")
     ap.add_argument("--overlap", action="store_true", help="miss gather on a second stream beside the hit gather")
     ap.add_argument("--no-pipeline", action="store_true",
                     help="skip the secondary measurement (sampling of batch i+1 beside feature extraction of batch i)")
@@ -105,6 +108,19 @@ def main() -> int:
     torch.cuda.synchronize()
     t_hot = time.time() - t0
     topo_b, feat_b = datagen.budgets(spec, E)
+    auto_plan = None
+    if args.cache_bytes:
+        topo_hot, _ = ctx.get_hotness()
+        # N_TSUM: pre-sampling reads one 128-byte line of column ids per vertex expansion; CLS = that line size
+        _, n_tsum = ctx.get_presample_stats()
+        best, pts = ctx.search_cache_plan(args.cache_bytes, n_tsum, cls_bytes=128)
+        pick = best if args.alpha is None else int(round(args.alpha * 100))
+        topo_b, feat_b = int(pts["m_topo"][pick]), int(pts["m_feat"][pick])
+        per_row = -(-row_bytes // 128)
+        all_t = max(int(topo_hot.sum()), 1)
+        auto_plan = {"B": args.cache_bytes, "alpha": pick / 100, "alpha_by_cost_model": best / 100,
+                     "predicted_N_total": round(n_tsum * int(pts["uncached_topo_hot"][pick]) / all_t
+                                                + per_row * int(pts["uncached_feat_hot"][pick]))}
     t0 = time.time()
     plan = ctx.build_cache(topo_b, feat_b)
     t_cache = time.time() - t0
@@ -309,7 +325,7 @@ def main() -> int:
         "config": {"workload": f"{spec.name}: V={V} E={E} D={D} {spec.feat_dtype} fanouts={list(spec.fanouts)} "
                                f"batch={spec.batch} topo_cache={spec.topo_frac:g} feat_cache={spec.feat_frac:g}"
                                + (" (source feature table in HBM)" if args.features_on_device else ""),
-                   "cached_topo_rows": plan.n_topo, "cached_feat_rows": plan.n_feat,
+                   "cached_topo_rows": plan.n_topo, "cached_feat_rows": plan.n_feat, "cache_plan": auto_plan,
                    "batches_in_tablet": n_batches},
         "roofline": roofline, "roofline_pcie": roofline_pcie, "cpu_baseline": cpu, "cpu_baseline_all_cores": cpu_all,
         "pipelined": pipelined, "graph_replay": graph_replay,

@@ -144,6 +144,13 @@ int lgp_build_hotness(lgp_ctx* ctx, const int32_t* train_ids, int64_t n_train, i
                       const int32_t* fanouts, int32_t n_hops, uint64_t base_seed, int64_t max_batches,
                       void* stream);
 
+/* What the last lgp_build_hotness did: mini-batches processed and vertex expansions performed
+ * (the sum of all frontier sizes).  During pre-sampling every expansion reads its column ids
+ * from CPU memory, so n_expansions is the exact count of row reads over PCIe -- on this GPU one
+ * 128-byte line each for all but very long rows -- and serves as N_TSUM for
+ * lgp_search_cache_plan (with cls_bytes = 128).  Synchronous. */
+int lgp_get_presample_stats(lgp_ctx* ctx, int64_t* n_batches, int64_t* n_expansions);
+
 /* Copy the hotness vectors (uint32[V] each) to / from [host] memory; either pointer
  * may be NULL.  Synchronous.  lgp_set_hotness lets a saved ranking be reused. */
 int lgp_get_hotness(lgp_ctx* ctx, uint32_t* topo_hot, uint32_t* feat_hot);

@@ -58,7 +58,7 @@ class Profile(C.Structure):
                 ("ms_miss", C.c_double)]
 
 
-EXPORTS = ["lgp_host_alloc", "lgp_host_free", "lgp_shuffle_tablet", "lgp_create", "lgp_destroy", "lgp_build_hotness", "lgp_get_hotness",
+EXPORTS = ["lgp_host_alloc", "lgp_host_free", "lgp_shuffle_tablet", "lgp_create", "lgp_destroy", "lgp_build_hotness", "lgp_get_presample_stats", "lgp_get_hotness",
            "lgp_set_hotness", "lgp_plan_cache", "lgp_search_cache_plan", "lgp_cslp", "lgp_build_cache", "lgp_get_cache_plan", "lgp_get_cache",
            "lgp_sample_khop", "lgp_build_blocks", "lgp_gather_features", "lgp_set_overlap", "lgp_check", "lgp_set_profiling", "lgp_get_profile",
            "lgp_strerror", "lgp_last_error"]
@@ -81,6 +81,7 @@ def load_library():
     L.lgp_create.argtypes = [C.POINTER(_Graph), C.c_int, C.POINTER(vp)]
     L.lgp_destroy.argtypes = [vp]
     L.lgp_build_hotness.argtypes = [vp, vp, i64, i32, vp, i32, u64, i64, vp]
+    L.lgp_get_presample_stats.argtypes = [vp, vp, vp]
     L.lgp_get_hotness.argtypes = [vp, vp, vp]
     L.lgp_set_hotness.argtypes = [vp, vp, vp]
     L.lgp_plan_cache.argtypes = [vp, u64, u64, C.POINTER(CachePlan), vp]
@@ -303,6 +304,12 @@ class Context:
         fo = self._fanouts(fanouts)
         self._ok(self._L.lgp_build_hotness(self._h, train_ids.data_ptr(), train_ids.numel(), batch, fo.ctypes.data,
                                            fo.size, base_seed & (2**64 - 1), max_batches, _stream_ptr(stream)))
+
+    def get_presample_stats(self):
+        """(n_batches, n_expansions) of the last build_hotness."""
+        nb, ne = C.c_int64(0), C.c_int64(0)
+        self._ok(self._L.lgp_get_presample_stats(self._h, C.addressof(nb), C.addressof(ne)))
+        return int(nb.value), int(ne.value)
 
     def get_hotness(self):
         topo = np.empty(self.num_vertices, dtype=np.uint32)

@@ -58,6 +58,8 @@ struct lgp_ctx {
   int32_t* hs_frontier[LGP_MAX_HOPS] = {};
   int64_t hs_cap[LGP_MAX_HOPS] = {};
   int32_t* hs_n = nullptr;
+  unsigned long long* hs_expansions = nullptr;   // device counter: sum of frontier sizes of the last pre-sampling
+  int64_t hs_batches = 0;
 
   hipStream_t miss_stream = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
@@ -371,7 +373,8 @@ int lgp_create(const lgp_graph* g, int device, lgp_ctx** out) {
   step(dev_alloc(&c->chunk_counts, size_t(c->n_chunks)));
   step(dev_alloc(&c->d_err, 1));
   step(dev_alloc(&c->counters, 2));
-  step(dev_alloc(&c->hs_n, LGP_MAX_HOPS));
+  step(dev_alloc(&c->hs_n, LGP_MAX_HOPS + 1));
+  step(dev_alloc(&c->hs_expansions, 1));
   if (e == hipSuccess) e = hipMemset(c->f_remap, 0xff, sizeof(int32_t) * size_t(V));
   if (e == hipSuccess) e = hipMemset(c->topo_hot, 0, sizeof(uint32_t) * size_t(V));
   if (e == hipSuccess) e = hipMemset(c->feat_hot, 0, sizeof(uint32_t) * size_t(V));
@@ -379,6 +382,7 @@ int lgp_create(const lgp_graph* g, int device, lgp_ctx** out) {
   if (e == hipSuccess) e = hipMemset(c->gbits, 0, sizeof(uint64_t) * words);
   if (e == hipSuccess) e = hipMemset(c->d_err, 0, sizeof(uint32_t));
   if (e == hipSuccess) e = hipMemset(c->counters, 0, 2 * sizeof(int32_t));
+  if (e == hipSuccess) e = hipMemset(c->hs_expansions, 0, sizeof(unsigned long long));
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->miss_stream, hipStreamNonBlocking);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming);
@@ -401,7 +405,7 @@ int lgp_destroy(lgp_ctx* c) {
   (void)hipDeviceSynchronize();
   free_cache(c);
   void* ptrs[] = {c->row_tab, c->f_remap, c->topo_hot, c->feat_hot, c->fbits, c->gbits, c->chunk_counts,
-                  c->d_err,   c->counters, c->order_t, c->order_f,  c->lists, c->hs_n, c->pos_table, c->tile_sums};
+                  c->d_err,   c->counters, c->order_t, c->order_f,  c->lists, c->hs_n, c->pos_table, c->tile_sums, c->hs_expansions};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   for (int h = 0; h < LGP_MAX_HOPS; ++h)
@@ -442,6 +446,7 @@ int lgp_build_hotness(lgp_ctx* c, const int32_t* train_ids, int64_t n_train, int
   }
   launch_fill_i32(c->di, reinterpret_cast<int32_t*>(c->topo_hot), V, 0, s);
   launch_fill_i32(c->di, reinterpret_cast<int32_t*>(c->feat_hot), V, 0, s);
+  launch_fill_i32(c->di, reinterpret_cast<int32_t*>(c->hs_expansions), 2, 0, s);
   int64_t n_batches = (n_train + batch - 1) / batch;
   if (max_batches >= 0 && max_batches < n_batches) n_batches = max_batches;
   for (int64_t b = 0; b < n_batches; ++b) {
@@ -449,8 +454,21 @@ int lgp_build_hotness(lgp_ctx* c, const int32_t* train_ids, int64_t n_train, int
     const int32_t nb = int32_t(std::min<int64_t>(batch, n_train - lo));
     st = sample_core(c, train_ids + lo, nb, fanouts, n_hops, base_seed + uint64_t(b), nullptr, s);
     if (st != LGP_OK) return st;
+    launch_accumulate_sizes(c->hs_n, n_hops, c->hs_expansions, s);
   }
+  c->hs_batches = n_batches;
   c->have_hot = true;
+  return LGP_OK;
+}
+
+int lgp_get_presample_stats(lgp_ctx* c, int64_t* n_batches, int64_t* n_expansions) {
+  if (!c) return LGP_EINVAL;
+  LGP_HIP(c, hipSetDevice(c->di.device));
+  LGP_HIP(c, hipDeviceSynchronize());
+  unsigned long long v = 0;
+  LGP_HIP(c, hipMemcpy(&v, c->hs_expansions, sizeof(v), hipMemcpyDeviceToHost));
+  if (n_batches) *n_batches = c->hs_batches;
+  if (n_expansions) *n_expansions = int64_t(v);
   return LGP_OK;
 }
 

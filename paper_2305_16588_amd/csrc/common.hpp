@@ -56,6 +56,9 @@ void launch_sample_hop(const DeviceInfo& di, const TopoView& tv, const int32_t* 
                        int64_t cap, int32_t fanout, int32_t hop, uint64_t rng_seed, int32_t* nbr, int32_t* cnt,
                        uint32_t* mark_bits, uint32_t* self_bits, uint32_t* topo_hot, uint32_t* d_err, hipStream_t s);
 
+// acc[0] += n[0] + ... + n[count - 1]   (frontier sizes of one pre-sampling batch)
+void launch_accumulate_sizes(const int32_t* n, int32_t count, unsigned long long* acc, hipStream_t s);
+
 // ---- compact.hip ----------------------------------------------------------
 // Turn the bitmap `bits` (n_chunks * kChunkWords 64-bit words) into the ascending id
 // list out[0 .. *n_out).  If or_into is given, bits are OR-ed into it; `bits` is

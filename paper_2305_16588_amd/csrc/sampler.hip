@@ -92,6 +92,15 @@ __global__ __launch_bounds__(256) void sample_hop_kernel(
   }
 }
 
+__global__ void accumulate_sizes_kernel(const int32_t* __restrict__ n, int32_t count,
+                                        unsigned long long* __restrict__ acc) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    unsigned long long sum = 0;
+    for (int32_t h = 0; h < count; ++h) sum += (unsigned long long)(n[h]);
+    acc[0] += sum;                                // one writer, stream-ordered
+  }
+}
+
 template <typename IdxT, int P>
 void launch_one(const DeviceInfo& di, const TopoView& tv, const int32_t* frontier, int32_t* n_frontier,
                 int64_t cap, int32_t f, int32_t hop, uint64_t seed, int32_t* nbr, int32_t* cnt, uint32_t* mark_bits,
@@ -135,6 +144,10 @@ void launch_sample_hop(const DeviceInfo& di, const TopoView& tv, const int32_t* 
   else
     dispatch_p<int32_t>(P, di, tv, frontier, n_frontier, cap, fanout, hop, rng_seed, nbr, cnt, mark_bits, self_bits,
                         topo_hot, d_err, s);
+}
+
+void launch_accumulate_sizes(const int32_t* n, int32_t count, unsigned long long* acc, hipStream_t s) {
+  hipLaunchKernelGGL(accumulate_sizes_kernel, dim3(1), dim3(64), 0, s, n, count, acc);
 }
 
 }  // namespace lgp

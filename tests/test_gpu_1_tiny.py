@@ -62,6 +62,11 @@ def test_hotness_whole_epoch(W):
     topo, feat = W.ctx.get_hotness()
     rt, rf, nb = W.orc.build_hotness(W.tablet, spec.batch, spec.fanouts, spec.base_seed, max_batches=3)
     assert nb == 3 and (topo == rt).all() and (feat == rf).all()
+    expansions = 0                                             # sum of all frontier sizes = row reads over PCIe
+    for b in range(3):
+        res = W.orc.sample_khop(W.batch(b)[0], spec.fanouts, spec.base_seed + b)
+        expansions += sum(res.frontier[h].size for h in range(len(spec.fanouts)))
+    assert W.ctx.get_presample_stats() == (3, expansions)
     W.ctx.check()
 
 
