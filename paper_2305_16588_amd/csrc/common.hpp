@@ -89,7 +89,6 @@ struct DirectIds {
 void launch_gather_rows(const DeviceInfo& di, const void* src, void* dst, int64_t row_bytes, const int32_t* row,
                         const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, bool streaming, hipStream_t s,
                         const DirectIds& dir = DirectIds{nullptr, 0, nullptr, 0, nullptr});
-void launch_copy_i32(const int32_t* src, int32_t* dst, int n, hipStream_t s);
 
 // ---- blocks.hip -----------------------------------------------------------
 constexpr int kScanTile = 1024;   // elements per workgroup of the counts -> offsets scan
@@ -111,7 +110,6 @@ struct CachePlan {
   int64_t n_topo = 0, topo_edges = 0, n_feat = 0;
   uint64_t topo_bytes = 0, feat_bytes = 0;
 };
-struct RankScratch;  // opaque, owned by cache.hip
 // Rank vertices by (hotness descending, id ascending) into order[V].  Synchronous parts
 // use `s`.  Returns hipSuccess or the failing HIP status.
 hipError_t rank_by_hotness(const uint32_t* hot, int64_t num_vertices, int32_t* order, hipStream_t s);

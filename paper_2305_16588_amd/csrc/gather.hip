@@ -262,10 +262,6 @@ void launch_group(const DeviceInfo& di, const void* src, void* dst, int64_t row_
   else launch_group_g<VecT, 64>(di, src, dst, cpr, row, srcrow, n_max, n_dev, dir, s);
 }
 
-__global__ void copy_i32_kernel(const int32_t* src, int32_t* dst, int n) {
-  if (int(threadIdx.x) < n) dst[threadIdx.x] = src[threadIdx.x];
-}
-
 }  // namespace
 
 void launch_partition(const DeviceInfo& di, const int32_t* ids, int64_t n_max, const int32_t* n_dev,
@@ -297,10 +293,6 @@ void launch_gather_rows(const DeviceInfo& di, const void* src, void* dst, int64_
   else if ((align & 3u) == 0) LGP_ROWS(uint32_t);
   else LGP_ROWS(uint16_t);
 #undef LGP_ROWS
-}
-
-void launch_copy_i32(const int32_t* src, int32_t* dst, int n, hipStream_t s) {
-  hipLaunchKernelGGL(copy_i32_kernel, dim3(1), dim3(64), 0, s, src, dst, n);
 }
 
 }  // namespace lgp

@@ -39,9 +39,9 @@ def main() -> None:
 
     # cache construction: pre-sampling -> cost model picks alpha -> fill
     ctx.build_hotness(tablet, spec.batch, spec.fanouts, spec.base_seed)
-    topo_hot, _ = ctx.get_hotness()
+    _, n_row_reads = ctx.get_presample_stats()          # N_TSUM: one 128-byte line per expansion on this GPU
     budget = int(args.cache_gb * 1e9)
-    best, pts = ctx.search_cache_plan(budget, n_tsum=int(topo_hot.sum()))
+    best, pts = ctx.search_cache_plan(budget, n_tsum=n_row_reads, cls_bytes=128)
     plan = ctx.build_cache(int(pts["m_topo"][best]), int(pts["m_feat"][best]))
     print(f"cache plan: alpha = {best / 100:.2f} -> {plan.n_topo} topology rows ({plan.topo_bytes / 1e6:.0f} MB), "
           f"{plan.n_feat} feature rows ({plan.feat_bytes / 1e6:.0f} MB)")
