@@ -31,7 +31,8 @@ def test_sampling_every_batch_of_the_epoch(W):
     W.ctx.check()
 
 
-@pytest.mark.parametrize("fanouts", [(1,), (64,), (3, 2, 2, 2), (25, 10), (15, 10, 5), (16, 8), (33, 2)])
+@pytest.mark.parametrize("fanouts", [(1,), (64,), (3, 2, 2, 2), (25, 10), (15, 10, 5), (16, 8), (33, 2), (2,) * 8,
+                                     (64, 64)])
 def test_sampling_fanout_shapes(W, fanouts):
     from gpu_common import assert_batch_equal
     seeds, seeds_dev = W.tablet[:300], W.tablet_dev[:300]
@@ -480,3 +481,55 @@ def test_row_wider_than_the_limit_is_refused():
     with pytest.raises(lgp.LegionPrepError) as e:
         lgp.Context(lgp.pinned_copy(indptr), lgp.pinned_copy(indices), feats)
     assert e.value.status == -4
+
+
+@pytest.mark.parametrize("case", range(24))
+def test_randomized_small_workloads(case):
+    """Random small graphs, feature widths, fan-out lists, seed sets and cache splits: sampling, blocks and
+    gathered bytes against the oracle."""
+    import oracle
+    import paper_2305_16588_amd as lgp
+    from gpu_common import assert_batch_equal, assert_blocks_equal
+    rng = np.random.default_rng(1000 + case)
+    V = int(rng.integers(1, 4000))
+    indptr, indices = datagen.tiny_graph(V, float(rng.uniform(0.0, 12.0)), case)
+    if rng.random() < 0.5:
+        indptr = indptr.astype(np.int64)
+    dim = int(rng.integers(1, 70))
+    npdt = np.float16 if rng.random() < 0.5 else np.float32
+    feats = lgp.pinned_empty((V, dim), npdt)
+    feats[...] = rng.standard_normal((V, dim)).astype(npdt)
+    p_indptr, p_indices = lgp.pinned_copy(indptr), lgp.pinned_copy(indices)
+    ctx = lgp.Context(p_indptr, p_indices, feats)
+    orc = oracle.Oracle(indptr, indices, feats)
+    fanouts = tuple(int(x) for x in rng.integers(1, 65, size=int(rng.integers(1, 5))))
+    tablet = rng.permutation(V).astype(np.int32)
+    batch = int(rng.integers(1, max(2, V // 2 + 1)))
+    tab_dev = torch.from_numpy(tablet).cuda()
+    ctx.build_hotness(tab_dev, batch, fanouts, case)
+    rt, rf, _ = orc.build_hotness(tablet, batch, fanouts, case)
+    gt, gf = ctx.get_hotness()
+    assert (gt == rt).all() and (gf == rf).all()
+    row_bytes = dim * np.dtype(npdt).itemsize
+    topo_b = int(rng.uniform(0, 1.2) * (4 * indices.size + 8 * V))
+    feat_b = int(rng.uniform(0, 1.2) * V) * row_bytes
+    plan = ctx.build_cache(topo_b, feat_b)
+    qt, qf = orc.rank_by_hotness(rt), orc.rank_by_hotness(rf)
+    assert (plan.n_topo, plan.n_feat) == (orc.plan_topo(qt, topo_b), orc.plan_feat(feat_b))
+    seeds = tablet[:batch]
+    dev = tab_dev[:batch].contiguous()
+    seed = int(rng.integers(0, 2**63))
+    buf = lgp.SampleBuffers(V, batch, fanouts, last_frontier=True)
+    ctx.sample_khop(dev, fanouts, seed, out=buf)
+    blk = ctx.build_blocks(dev, fanouts, buf)
+    stats = torch.zeros(2, dtype=torch.int32, device="cuda")
+    rows = ctx.gather_features(buf.gather_ids, n_dev=buf.n_gather, stats=stats)
+    ref = orc.sample_khop(seeds, fanouts, seed, blocks=True)
+    assert_batch_equal(ref, buf.to_host(dev), f"case {case}")
+    assert_blocks_equal(ref, blk.to_host(), f"case {case}")
+    n = ref.gather_ids.size
+    assert rows[:n].cpu().numpy().tobytes() == orc.gather(ref.gather_ids).tobytes()
+    n_hit = orc.count_hits(ref.gather_ids, qf, plan.n_feat)
+    assert stats.tolist() == [n_hit, n - n_hit]
+    ctx.check()
+    ctx.close()
