@@ -161,8 +161,9 @@ int lgp_set_hotness(lgp_ctx* ctx, const uint32_t* topo_hot, const uint32_t* feat
  * id).  The topology cache takes the longest prefix of the topology ranking whose
  * cost sum(deg * 4 + 8) stays within topo_budget (Eq. 3); the feature cache takes
  * min(V, feat_budget / (D * elem_bytes)) rows of the feature ranking (Eq. 6).  Rows
- * are copied from CPU memory in rank order; cache slot = rank.  Replaces any earlier
- * cache.  Needs hotness (LGP_ESTATE otherwise).  Allocates device memory and
+ * are copied from CPU memory in rank order; cache slot = rank (one exception, invisible
+ * through this interface: a feature cache that holds every vertex is laid out in vertex
+ * order, so that no lookup is needed to find a row).  Replaces any earlier cache.  Needs hotness (LGP_ESTATE otherwise).  Allocates device memory and
  * synchronises `stream`.  lgp_plan_cache only reports the sizes. */
 int lgp_plan_cache(lgp_ctx* ctx, uint64_t topo_budget, uint64_t feat_budget, lgp_cache_plan* plan, void* stream);
 int lgp_build_cache(lgp_ctx* ctx, uint64_t topo_budget, uint64_t feat_budget, void* stream);

@@ -43,6 +43,7 @@ struct lgp_ctx {
   int64_t* t_indptr = nullptr;
   int32_t* t_indices = nullptr;
   void* fc = nullptr;
+  bool fc_identity = false;   // the feature cache holds every vertex, laid out in vertex order (slot = id)
   CachePlan plan;
 
   // gather scratch: hit / miss lists
@@ -129,6 +130,7 @@ void free_cache(lgp_ctx* c) {
   c->t_indptr = nullptr;
   c->t_indices = nullptr;
   c->fc = nullptr;
+  c->fc_identity = false;
   c->plan = CachePlan();
 }
 
@@ -633,7 +635,11 @@ int lgp_build_cache(lgp_ctx* c, uint64_t topo_budget, uint64_t feat_budget, void
     launch_fill_topo(c->di, c->g.indptr, c->g.indptr_bytes, c->g.indices, c->order_t, p.n_topo, c->t_indptr,
                      c->t_indices, s);
     launch_set_cached_rows(c->di, c->order_t, p.n_topo, c->t_indptr, c->row_tab, s);
-    if (p.n_feat > 0) {
+    if (p.n_feat == V) {
+      // the whole table fits: keep vertex order, so a cached row is found without any lookup
+      launch_gather_rows(c->di, c->g.features, c->fc, c->row_bytes, nullptr, nullptr, V, nullptr, true, s);
+      launch_iota_i32(c->di, c->f_remap, V, s);
+    } else if (p.n_feat > 0) {
       launch_gather_rows(c->di, c->g.features, c->fc, c->row_bytes, nullptr, c->order_f, p.n_feat, nullptr, true, s);
       launch_scatter_rank(c->di, c->order_f, p.n_feat, c->f_remap, s);
     }
@@ -650,6 +656,7 @@ int lgp_build_cache(lgp_ctx* c, uint64_t topo_budget, uint64_t feat_budget, void
     return st;
   }
   c->plan = p;
+  c->fc_identity = (p.n_feat == V);
   return LGP_OK;
 }
 
@@ -682,7 +689,27 @@ int lgp_get_cache(lgp_ctx* c, int32_t* topo_ids, int64_t* t_indptr, int32_t* t_i
     LGP_HIP(c, hipMemcpy(t_indices, c->t_indices, sizeof(int32_t) * size_t(p.topo_edges), hipMemcpyDeviceToHost));
   if (feat_ids && p.n_feat)
     LGP_HIP(c, hipMemcpy(feat_ids, c->order_f, sizeof(int32_t) * size_t(p.n_feat), hipMemcpyDeviceToHost));
-  if (feat_rows && p.n_feat) LGP_HIP(c, hipMemcpy(feat_rows, c->fc, size_t(p.feat_bytes), hipMemcpyDeviceToHost));
+  if (feat_rows && p.n_feat) {
+    if (!c->fc_identity) {
+      LGP_HIP(c, hipMemcpy(feat_rows, c->fc, size_t(p.feat_bytes), hipMemcpyDeviceToHost));
+    } else {
+      // the cache sits in vertex order; hand it out in rank order like any other cache
+      const int64_t chunk = std::max<int64_t>(1, std::min<int64_t>(p.n_feat, (int64_t(256) << 20) / c->row_bytes));
+      void* tmp = nullptr;
+      LGP_HIP(c, hipMalloc(&tmp, size_t(chunk * c->row_bytes)));
+      hipError_t e = hipSuccess;
+      for (int64_t lo = 0; lo < p.n_feat && e == hipSuccess; lo += chunk) {
+        const int64_t n = std::min(chunk, p.n_feat - lo);
+        launch_gather_rows(c->di, c->fc, tmp, c->row_bytes, nullptr, c->order_f + lo, n, nullptr, false, nullptr);
+        e = hipGetLastError();
+        if (e == hipSuccess)
+          e = hipMemcpy(static_cast<char*>(feat_rows) + lo * c->row_bytes, tmp, size_t(n * c->row_bytes),
+                        hipMemcpyDeviceToHost);
+      }
+      (void)hipFree(tmp);
+      if (e != hipSuccess) return fail_hip(c, e, "reading the feature cache back");
+    }
+  }
   return LGP_OK;
 }
 
@@ -794,7 +821,7 @@ int lgp_gather_features(lgp_ctx* c, const int32_t* ids, int64_t n_max, const int
     // every row is cached: no partition, the id list is looked up by the gather itself
     ev = prof_begin(c, PK_HIT, s);
     launch_gather_rows(c->di, c->fc, out, c->row_bytes, nullptr, ids, n_max, n_dev, false, s,
-                       DirectIds{c->f_remap, V, counters, 0, c->d_err});
+                       DirectIds{c->fc_identity ? nullptr : c->f_remap, V, counters, 0, c->d_err});
     prof_end(c, ev, s);
   } else if (c->plan.n_feat == 0) {
     // nothing is cached: every id is its own source row in CPU memory

@@ -191,6 +191,11 @@ __global__ void fill_i32_kernel(int32_t* __restrict__ p, int64_t n, int32_t valu
     p[k] = value;
 }
 
+__global__ void iota_i32_kernel(int32_t* __restrict__ p, int64_t n) {
+  for (int64_t k = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; k < n; k += int64_t(gridDim.x) * blockDim.x)
+    p[k] = int32_t(k);
+}
+
 __global__ void scatter_rank_kernel(const int32_t* __restrict__ order, int64_t n, int32_t* __restrict__ remap) {
   for (int64_t r = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; r < n; r += int64_t(gridDim.x) * blockDim.x)
     remap[order[r]] = int32_t(r);
@@ -372,6 +377,10 @@ void launch_set_cached_rows(const DeviceInfo& di, const int32_t* order, int64_t 
   if (n_topo <= 0) return;
   hipLaunchKernelGGL(set_cached_rows_kernel, dim3(grid_for(di, n_topo)), dim3(256), 0, s, order, n_topo, t_indptr,
                      row_tab);
+}
+
+void launch_iota_i32(const DeviceInfo& di, int32_t* p, int64_t n, hipStream_t s) {
+  hipLaunchKernelGGL(iota_i32_kernel, dim3(grid_for(di, n)), dim3(256), 0, s, p, n);
 }
 
 void launch_scatter_rank(const DeviceInfo& di, const int32_t* order, int64_t n, int32_t* remap, hipStream_t s) {

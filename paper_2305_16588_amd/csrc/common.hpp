@@ -84,7 +84,7 @@ struct DirectIds {
 };
 
 // dst[row[e], :] = src[srcrow[e], :] for e < *n_dev (or n_max if n_dev is null); rows are
-// row_bytes wide; `row` may be null (row = e).  streaming = source is read once over
+// row_bytes wide; `row` and `srcrow` may each be null (= e).  streaming = source is read once over
 // PCIe (non-temporal loads, one lane group per row).
 void launch_gather_rows(const DeviceInfo& di, const void* src, void* dst, int64_t row_bytes, const int32_t* row,
                         const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, bool streaming, hipStream_t s,
@@ -152,6 +152,8 @@ void launch_init_row_table(const DeviceInfo& di, const void* h_indptr, int32_t i
 // row_tab[order[r]] = (cached, t_indptr[r], degree) for r < n_topo (rows too long to pack keep their CPU entry).
 void launch_set_cached_rows(const DeviceInfo& di, const int32_t* order, int64_t n_topo, const int64_t* t_indptr,
                             uint64_t* row_tab, hipStream_t s);
+// p[k] = k for k < n.
+void launch_iota_i32(const DeviceInfo& di, int32_t* p, int64_t n, hipStream_t s);
 // remap[order[r]] = r for r < n.
 void launch_scatter_rank(const DeviceInfo& di, const int32_t* order, int64_t n, int32_t* remap, hipStream_t s);
 

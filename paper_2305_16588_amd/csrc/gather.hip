@@ -124,7 +124,7 @@ __global__ __launch_bounds__(256) void gather_rows_flat_kernel(const VecT* __res
   for (int64_t e0 = wave * 64; e0 < n; e0 += n_waves * 64) {
     const int64_t e = e0 + lane;
     const int32_t my_row = e < n ? (row ? row[e] : int32_t(e)) : 0;
-    const int32_t my_src = direct_source(dir, e < n ? srcrow[e] : 0, e < n);
+    const int32_t my_src = direct_source(dir, e < n ? (srcrow ? srcrow[e] : int32_t(e)) : 0, e < n);
     const uint32_t entries = uint32_t(n - e0 < 64 ? n - e0 : 64);
     const uint32_t total = entries * cpr;          // chunks in this wave's 64 rows
     for (uint32_t f0 = 0; f0 < total; f0 += 64 * UNROLL) {
@@ -175,7 +175,7 @@ __global__ __launch_bounds__(256) void gather_rows_group_kernel(const VecT* __re
     for (int u = 0; u < UNROLL; ++u) {
       const int64_t e = e0 + u;
       const bool ok = e < n;
-      const int32_t sr = direct_source(dir, ok ? srcrow[e] : 0, ok);
+      const int32_t sr = direct_source(dir, ok ? (srcrow ? srcrow[e] : int32_t(e)) : 0, ok);
       so[u] = sr >= 0 ? int64_t(sr) * cpr : -1;
       dof[u] = ok ? int64_t(row ? row[e] : int32_t(e)) * cpr : 0;
     }
