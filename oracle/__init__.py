@@ -85,6 +85,12 @@ def _load():
         L.orc_shuffle_tablet.restype = None
         L.orc_cslp.argtypes = [i32, i64, vp, vp, vp, vp, vp, vp]
         L.orc_cslp.restype = None
+        L.orc_queue_prefix_topo.argtypes = [gp, vp, i64, u64]
+        L.orc_queue_prefix_topo.restype = i64
+        L.orc_queue_prefix_feat.argtypes = [i64, i64, u64]
+        L.orc_queue_prefix_feat.restype = i64
+        L.orc_count_three_way.argtypes = [vp, i64, vp, i32, vp]
+        L.orc_count_three_way.restype = None
         _lib = L
     return _lib
 
@@ -250,6 +256,32 @@ class Oracle:
         best = self._L.orc_search_cache_plan(C.byref(self._g), _p(topo_hot), _p(feat_hot), _p(order_t), _p(order_f),
                                              self.row_bytes, int(total_budget), int(n_tsum), cls, n_alpha, _p(points))
         return int(best), points
+
+    def clique_plan(self, topo_hot: np.ndarray, feat_hot: np.ndarray, topo_budget: int, feat_budget: int):
+        """Caches of a clique: topo_hot / feat_hot are [k_g, V] hotness matrices, the budgets are per GPU.
+        Returns (topo_ids, feat_ids): per GPU, the vertex ids its caches hold, in fill order."""
+        topo_ids, feat_ids = [], []
+        _, _, _, queues, offsets = cslp(topo_hot)
+        for g in range(offsets.size - 1):
+            q = np.ascontiguousarray(queues[offsets[g]:offsets[g + 1]])
+            n = int(self._L.orc_queue_prefix_topo(C.byref(self._g), _p(q), q.size, int(topo_budget))) if q.size else 0
+            topo_ids.append(q[:n].copy())
+        _, _, _, queues, offsets = cslp(feat_hot)
+        for g in range(offsets.size - 1):
+            q = queues[offsets[g]:offsets[g + 1]]
+            n = int(self._L.orc_queue_prefix_feat(q.size, self.row_bytes, int(feat_budget)))
+            feat_ids.append(q[:n].copy())
+        return topo_ids, feat_ids
+
+    def count_three_way(self, ids: np.ndarray, feat_ids: list, member: int):
+        """(local hits, misses, peer hits) of an id list for GPU `member`, given every GPU's cached feature ids."""
+        ids = np.ascontiguousarray(ids, dtype=np.int32)
+        cached_by = np.full(self.V, -1, dtype=np.int32)
+        for g, f in enumerate(feat_ids):
+            cached_by[f] = g
+        counts = np.zeros(3, dtype=np.int64)
+        self._L.orc_count_three_way(_p(ids), ids.size, _p(cached_by), member, _p(counts))
+        return int(counts[0]), int(counts[1]), int(counts[2])
 
     def count_hits(self, ids: np.ndarray, order: np.ndarray, n_cached: int) -> int:
         ids = np.ascontiguousarray(ids, dtype=np.int32)

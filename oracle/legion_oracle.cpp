@@ -377,6 +377,48 @@ void orc_cslp(int32_t k_g, int64_t num_vertices, const uint32_t* hot, uint64_t* 
   offsets[k_g] = at;
 }
 
+// --- cache of a clique of k_g GPUs (Sec. 4.2.2: the queues of S2 drive the fill-up of S3) ---
+// GPU g fills its own cache in the order of its own queue until its budget is used up.  The
+// paper does not say where a queue is cut: as for one GPU (Eq. 3), the longest prefix whose
+// rows (4 bytes per neighbour + 8 per row) fit.  Returns the number of queue entries taken.
+int64_t orc_queue_prefix_topo(const orc_graph* g, const int32_t* queue, int64_t len, uint64_t topo_budget) {
+  const Graph G = to_graph(g);
+  uint64_t used = 0;
+  int64_t n = 0;
+  for (; n < len; ++n) {
+    const int64_t v = queue[n];
+    const uint64_t cost = static_cast<uint64_t>(row_begin(G, v + 1) - row_begin(G, v)) * 4u + 8u;
+    if (used + cost > topo_budget) break;
+    used += cost;
+  }
+  return n;
+}
+
+// Feature rows all cost the same (Eq. 6): the first floor(budget / row_bytes) entries of the queue.
+int64_t orc_queue_prefix_feat(int64_t len, int64_t row_bytes, uint64_t feat_budget) {
+  uint64_t used = 0;
+  int64_t n = 0;
+  for (; n < len; ++n) {
+    if (used + static_cast<uint64_t>(row_bytes) > feat_budget) break;
+    used += static_cast<uint64_t>(row_bytes);
+  }
+  return n;
+}
+
+// Feature extraction as GPU `member` of the clique sees it (Sec. 3.1, O1: a GPU reads its
+// clique peers' caches over the fast links).  cached_by[v] = GPU whose cache holds v's row, or
+// -1.  counts[0] = rows found in the member's own cache, counts[1] = rows in no cache of the
+// clique (read from CPU memory), counts[2] = rows found in a peer's cache.
+void orc_count_three_way(const int32_t* ids, int64_t n, const int32_t* cached_by, int32_t member, int64_t* counts) {
+  counts[0] = counts[1] = counts[2] = 0;
+  for (int64_t i = 0; i < n; ++i) {
+    const int32_t where = cached_by[ids[i]];
+    if (where < 0) ++counts[1];
+    else if (where == member) ++counts[0];
+    else ++counts[2];
+  }
+}
+
 // --- cost model and alpha search (Sec. 4.3.2 Eq. 2-8, Sec. 4.3.3) -----------
 struct orc_plan_point {
   uint64_t m_topo, m_feat;          // bytes given to the two caches at this alpha
