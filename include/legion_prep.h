@@ -201,6 +201,36 @@ int lgp_search_cache_plan(lgp_ctx* ctx, uint64_t total_budget, uint64_t n_tsum, 
 int lgp_cslp(int device, int32_t k_g, int64_t num_vertices, const uint32_t* hot, uint64_t* acc, int32_t* order,
              int32_t* owner, int32_t* queues, int64_t* queue_offsets, void* stream);
 
+/* Unified cache of a whole clique of k_g GPUs, held by this one device (Sec. 4.2.2, S2 and
+ * S3, for K_g > 1; Sec. 3.1, O1: GPUs of a clique read one another's caches).  The k_g
+ * member GPUs are simulated: each member's cache is a region of its own in this device's HBM,
+ * so a "peer" read is a read of another region.  topo_hot and feat_hot [device] are the
+ * k_g x V hotness matrices H_T and H_F, row-major (one row per member; lgp_build_hotness on
+ * the member's tablet followed by lgp_get_hotness yields a row).  Algorithm 1 turns each
+ * matrix into k_g queues; member g then fills its topology cache with the longest prefix of
+ * its queue G_T[g] whose Eq. 3 cost fits topo_budget bytes, and its feature cache with the
+ * first floor(feat_budget / row_bytes) entries of G_F[g] -- both budgets are per member.  No
+ * vertex is cached twice.  Replaces any earlier cache; afterwards lgp_sample_khop reads
+ * every member's cached rows from HBM, lgp_gather_features counts a row cached by any
+ * member as a hit, lgp_get_cache returns the members' parts end to end (member 0 first, each
+ * in fill order) and lgp_get_cache_plan their totals.  1 <= k_g <= LGP_MAX_CLIQUE.
+ * Synchronous. */
+#define LGP_MAX_CLIQUE 8
+int lgp_build_clique_cache(lgp_ctx* ctx, int32_t k_g, const uint32_t* topo_hot, const uint32_t* feat_hot,
+                           uint64_t topo_budget, uint64_t feat_budget, void* stream);
+
+/* What member `member` of the clique cache holds (its share of lgp_get_cache's arrays starts
+ * where the shares of the members before it end).  LGP_ESTATE without a clique cache. */
+int lgp_get_clique_plan(lgp_ctx* ctx, int32_t member, lgp_cache_plan* plan);
+
+/* Feature extraction as member `member` of the clique sees it: like lgp_gather_features, but
+ * the ids are split three ways -- rows in the member's own cache, rows in a peer's cache (both
+ * HBM reads here, gathered by separate launches) and rows in no cache (read in place from CPU
+ * memory).  stats [device int32[3], may be NULL] receives {n_local, n_miss, n_peer}.
+ * LGP_ESTATE without a clique cache. */
+int lgp_gather_features_clique(lgp_ctx* ctx, int32_t member, const int32_t* ids, int64_t n_max, const int32_t* n_dev,
+                               void* out, int32_t* stats, void* stream);
+
 /* Copy the cache to [host] memory for inspection; any pointer may be NULL.
  * topo_ids[n_topo], t_indptr[n_topo + 1], t_indices[topo_edges], feat_ids[n_feat],
  * feat_rows[n_feat * D * elem_bytes].  Synchronous. */

@@ -59,7 +59,8 @@ class Profile(C.Structure):
 
 
 EXPORTS = ["lgp_host_alloc", "lgp_host_free", "lgp_shuffle_tablet", "lgp_create", "lgp_destroy", "lgp_build_hotness", "lgp_get_presample_stats", "lgp_get_hotness",
-           "lgp_set_hotness", "lgp_plan_cache", "lgp_search_cache_plan", "lgp_cslp", "lgp_build_cache", "lgp_get_cache_plan", "lgp_get_cache",
+           "lgp_set_hotness", "lgp_plan_cache", "lgp_search_cache_plan", "lgp_cslp", "lgp_build_cache", "lgp_build_clique_cache", "lgp_get_clique_plan",
+           "lgp_gather_features_clique", "lgp_get_cache_plan", "lgp_get_cache",
            "lgp_sample_khop", "lgp_build_blocks", "lgp_gather_features", "lgp_set_overlap", "lgp_check", "lgp_set_profiling", "lgp_get_profile",
            "lgp_strerror", "lgp_last_error"]
 
@@ -91,6 +92,9 @@ def load_library():
     L.lgp_build_cache.argtypes = [vp, u64, u64, vp]
     L.lgp_get_cache_plan.argtypes = [vp, C.POINTER(CachePlan)]
     L.lgp_get_cache.argtypes = [vp, vp, vp, vp, vp, vp]
+    L.lgp_build_clique_cache.argtypes = [vp, i32, vp, vp, u64, u64, vp]
+    L.lgp_get_clique_plan.argtypes = [vp, i32, C.POINTER(CachePlan)]
+    L.lgp_gather_features_clique.argtypes = [vp, i32, vp, i64, vp, vp, vp, vp]
     L.lgp_sample_khop.argtypes = [vp, vp, i32, vp, i32, u64, C.POINTER(_SampleOut), vp]
     L.lgp_build_blocks.argtypes = [vp, vp, i32, vp, i32, C.POINTER(_SampleOut), C.POINTER(_BlocksOut), vp]
     L.lgp_gather_features.argtypes = [vp, vp, i64, vp, vp, vp, vp]
@@ -343,6 +347,23 @@ class Context:
         self._ok(self._L.lgp_build_cache(self._h, int(topo_budget), int(feat_budget), _stream_ptr(stream)))
         return self.get_cache_plan()
 
+    def build_clique_cache(self, topo_hot: torch.Tensor, feat_hot: torch.Tensor, topo_budget: int, feat_budget: int,
+                           stream=None) -> list:
+        """Cache of a simulated clique from two [k_g, V] hotness matrices; budgets are per member.
+        Returns the members' plans."""
+        for h in (topo_hot, feat_hot):
+            assert h.is_cuda and h.is_contiguous() and h.dim() == 2 and h.shape[1] == self.num_vertices
+            assert h.dtype in (torch.int32, torch.uint32) and h.shape[0] == topo_hot.shape[0]
+        k_g = topo_hot.shape[0]
+        self._ok(self._L.lgp_build_clique_cache(self._h, k_g, topo_hot.data_ptr(), feat_hot.data_ptr(),
+                                                int(topo_budget), int(feat_budget), _stream_ptr(stream)))
+        return [self.get_clique_plan(g) for g in range(k_g)]
+
+    def get_clique_plan(self, member: int) -> CachePlan:
+        p = CachePlan()
+        self._ok(self._L.lgp_get_clique_plan(self._h, member, C.byref(p)))
+        return p
+
     def get_cache_plan(self) -> CachePlan:
         p = CachePlan()
         self._ok(self._L.lgp_get_cache_plan(self._h, C.byref(p)))
@@ -390,6 +411,21 @@ class Context:
         self._ok(self._L.lgp_gather_features(self._h, ids.data_ptr(), n_max,
                                              None if n_dev is None else n_dev.data_ptr(), out.data_ptr(),
                                              None if stats is None else stats.data_ptr(), _stream_ptr(stream)))
+        return out
+
+    def gather_features_clique(self, member: int, ids: torch.Tensor, n_dev: torch.Tensor | None = None,
+                               out: torch.Tensor | None = None, stats: torch.Tensor | None = None,
+                               stream=None) -> torch.Tensor:
+        """gather_features as clique member `member`; stats (int32[3]) = {n_local, n_miss, n_peer}."""
+        assert ids.is_cuda and ids.dtype == torch.int32 and ids.is_contiguous()
+        n_max = ids.numel()
+        if out is None:
+            out = torch.empty((n_max, self.feat_dim), dtype=self.feat_torch_dtype, device=self.device)
+        assert out.is_cuda and out.is_contiguous() and out.numel() * out.element_size() >= n_max * self.feat_dim * self.elem_bytes
+        assert stats is None or (stats.is_cuda and stats.dtype == torch.int32 and stats.numel() >= 3)
+        self._ok(self._L.lgp_gather_features_clique(self._h, member, ids.data_ptr(), n_max,
+                                                    None if n_dev is None else n_dev.data_ptr(), out.data_ptr(),
+                                                    None if stats is None else stats.data_ptr(), _stream_ptr(stream)))
         return out
 
     def check(self, stream=None):

@@ -35,7 +35,7 @@ struct lgp_ctx {
   uint64_t* gbits = nullptr;   // gather-set dedup bitmap
   int32_t* chunk_counts = nullptr;
   uint32_t* d_err = nullptr;
-  int32_t* counters = nullptr;  // {n_hit, n_miss}
+  int32_t* counters = nullptr;  // {n_hit, n_miss, n_peer}
 
   // caches
   int32_t* order_t = nullptr;
@@ -45,8 +45,14 @@ struct lgp_ctx {
   void* fc = nullptr;
   bool fc_identity = false;   // the feature cache holds every vertex, laid out in vertex order (slot = id)
   CachePlan plan;
+  // clique cache: member g holds cached vertices [clique_tn[g], clique_tn[g+1]) of order_t (edges
+  // [clique_te[g], clique_te[g+1]) of t_indices) and feature slots [clique_fn[g], clique_fn[g+1])
+  int32_t clique_k = 0;         // 0 = the cache was built for one GPU
+  int64_t clique_tn[LGP_MAX_CLIQUE + 1] = {};
+  int64_t clique_te[LGP_MAX_CLIQUE + 1] = {};
+  int64_t clique_fn[LGP_MAX_CLIQUE + 1] = {};
 
-  // gather scratch: hit / miss lists
+  // gather scratch: hit / miss / peer-hit lists
   int32_t* lists = nullptr;
   int64_t list_cap = 0;
 
@@ -132,6 +138,7 @@ void free_cache(lgp_ctx* c) {
   c->fc = nullptr;
   c->fc_identity = false;
   c->plan = CachePlan();
+  c->clique_k = 0;
 }
 
 TopoView topo_view(const lgp_ctx* c) {
@@ -374,7 +381,7 @@ int lgp_create(const lgp_graph* g, int device, lgp_ctx** out) {
   step(dev_alloc(&c->gbits, words));
   step(dev_alloc(&c->chunk_counts, size_t(c->n_chunks)));
   step(dev_alloc(&c->d_err, 1));
-  step(dev_alloc(&c->counters, 2));
+  step(dev_alloc(&c->counters, 3));
   step(dev_alloc(&c->hs_n, LGP_MAX_HOPS + 1));
   step(dev_alloc(&c->hs_expansions, 1));
   if (e == hipSuccess) e = hipMemset(c->f_remap, 0xff, sizeof(int32_t) * size_t(V));
@@ -383,7 +390,7 @@ int lgp_create(const lgp_graph* g, int device, lgp_ctx** out) {
   if (e == hipSuccess) e = hipMemset(c->fbits, 0, sizeof(uint64_t) * words);
   if (e == hipSuccess) e = hipMemset(c->gbits, 0, sizeof(uint64_t) * words);
   if (e == hipSuccess) e = hipMemset(c->d_err, 0, sizeof(uint32_t));
-  if (e == hipSuccess) e = hipMemset(c->counters, 0, 2 * sizeof(int32_t));
+  if (e == hipSuccess) e = hipMemset(c->counters, 0, 3 * sizeof(int32_t));
   if (e == hipSuccess) e = hipMemset(c->hs_expansions, 0, sizeof(unsigned long long));
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->miss_stream, hipStreamNonBlocking);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming);
@@ -660,6 +667,134 @@ int lgp_build_cache(lgp_ctx* c, uint64_t topo_budget, uint64_t feat_budget, void
   return LGP_OK;
 }
 
+int lgp_build_clique_cache(lgp_ctx* c, int32_t k_g, const uint32_t* topo_hot, const uint32_t* feat_hot,
+                           uint64_t topo_budget, uint64_t feat_budget, void* stream) {
+  if (!c) return LGP_EINVAL;
+  if (k_g < 1 || !topo_hot || !feat_hot) return fail(c, LGP_EINVAL, "k_g / topo_hot / feat_hot");
+  if (k_g > LGP_MAX_CLIQUE) return fail(c, LGP_EUNSUPPORTED, "more than LGP_MAX_CLIQUE members");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  LGP_HIP(c, hipSetDevice(c->di.device));
+  const int64_t V = c->g.num_vertices;
+  LGP_HIP(c, hipStreamSynchronize(s));
+  LGP_HIP(c, hipStreamSynchronize(c->miss_stream));
+  free_cache(c);
+  launch_init_row_table(c->di, c->g.indptr, c->g.indptr_bytes, V, c->row_tab, s);
+  launch_fill_i32(c->di, c->f_remap, V, -1, s);
+  if (!c->order_t) LGP_HIP(c, dev_alloc(&c->order_t, size_t(V)));
+  if (!c->order_f) LGP_HIP(c, dev_alloc(&c->order_f, size_t(V)));
+
+  uint64_t *acc = nullptr, *scan = nullptr, *result = nullptr;
+  int32_t *order = nullptr, *owner = nullptr, *queues = nullptr, *deg = nullptr;
+  unsigned long long* counts = nullptr;
+  int64_t tn[LGP_MAX_CLIQUE + 1] = {}, te[LGP_MAX_CLIQUE + 1] = {}, fn[LGP_MAX_CLIQUE + 1] = {};
+  unsigned long long host_counts[LGP_MAX_CLIQUE] = {};
+  hipError_t e = dev_alloc(&acc, size_t(V));
+  if (e == hipSuccess) e = dev_alloc(&scan, size_t(V));
+  if (e == hipSuccess) e = dev_alloc(&result, 2);
+  if (e == hipSuccess) e = dev_alloc(&order, size_t(V));
+  if (e == hipSuccess) e = dev_alloc(&owner, size_t(V));
+  if (e == hipSuccess) e = dev_alloc(&queues, size_t(V));
+  if (e == hipSuccess) e = dev_alloc(&deg, size_t(V));
+  if (e == hipSuccess) e = dev_alloc(&counts, size_t(k_g));
+
+  // topology: Algorithm 1 on H_T, then every member's queue is cut at its own budget (Eq. 3)
+  if (e == hipSuccess) e = cslp_rank(c->di, k_g, V, topo_hot, acc, order, owner, queues, counts, s);
+  if (e == hipSuccess) e = hipMemcpy(host_counts, counts, sizeof(unsigned long long) * size_t(k_g), hipMemcpyDeviceToHost);
+  if (e == hipSuccess) launch_degrees(c->di, c->g.indptr, c->g.indptr_bytes, V, deg, s);
+  int64_t q0 = 0;
+  for (int32_t g = 0; g < k_g && e == hipSuccess; ++g) {
+    const int64_t len = int64_t(host_counts[g]);
+    uint64_t host_result[2] = {0, 0};
+    if (len > 0) {
+      e = scan_topo_cost(deg, queues + q0, len, scan, s);
+      if (e == hipSuccess) {
+        launch_prefix_within_budget(scan, len, topo_budget, result, s);
+        e = hipMemcpyAsync(host_result, result, sizeof(host_result), hipMemcpyDeviceToHost, s);
+      }
+      if (e == hipSuccess) e = hipStreamSynchronize(s);
+    }
+    const int64_t n_g = int64_t(host_result[0]);
+    if (e == hipSuccess && n_g > 0)
+      e = hipMemcpyAsync(c->order_t + tn[g], queues + q0, sizeof(int32_t) * size_t(n_g), hipMemcpyDeviceToDevice, s);
+    tn[g + 1] = tn[g] + n_g;
+    te[g + 1] = te[g] + int64_t((host_result[1] - 8u * host_result[0]) / 4u);
+    q0 += len;
+  }
+  const int64_t n_topo = tn[k_g], topo_edges = te[k_g];
+  if (e == hipSuccess && n_topo > 0) e = scan_topo_cost(deg, c->order_t, n_topo, scan, s);
+  if (e == hipSuccess) e = dev_alloc(&c->t_indptr, size_t(n_topo + 1));
+  if (e == hipSuccess) e = dev_alloc(&c->t_indices, size_t(topo_edges));
+  if (e == hipSuccess) {
+    launch_topo_offsets(c->di, scan, n_topo, c->t_indptr, s);
+    launch_fill_topo(c->di, c->g.indptr, c->g.indptr_bytes, c->g.indices, c->order_t, n_topo, c->t_indptr,
+                     c->t_indices, s);
+    launch_set_cached_rows(c->di, c->order_t, n_topo, c->t_indptr, c->row_tab, s);
+    e = hipGetLastError();
+  }
+
+  // features: Algorithm 1 on H_F; every row costs the same (Eq. 6), so a member takes the head of its queue
+  if (e == hipSuccess && c->g.features && c->row_bytes > 0) {
+    e = cslp_rank(c->di, k_g, V, feat_hot, acc, order, owner, queues, counts, s);
+    if (e == hipSuccess)
+      e = hipMemcpy(host_counts, counts, sizeof(unsigned long long) * size_t(k_g), hipMemcpyDeviceToHost);
+    q0 = 0;
+    for (int32_t g = 0; g < k_g && e == hipSuccess; ++g) {
+      const int64_t len = int64_t(host_counts[g]);
+      const int64_t n_g = std::min<int64_t>(len, int64_t(feat_budget / uint64_t(c->row_bytes)));
+      if (n_g > 0)
+        e = hipMemcpyAsync(c->order_f + fn[g], queues + q0, sizeof(int32_t) * size_t(n_g), hipMemcpyDeviceToDevice, s);
+      fn[g + 1] = fn[g] + n_g;
+      q0 += len;
+    }
+    const int64_t n_feat = fn[k_g];
+    if (e == hipSuccess && n_feat > 0) e = hipMalloc(&c->fc, size_t(n_feat) * size_t(c->row_bytes));
+    if (e == hipSuccess && n_feat > 0) {
+      launch_gather_rows(c->di, c->g.features, c->fc, c->row_bytes, nullptr, c->order_f, n_feat, nullptr, true, s);
+      launch_scatter_rank(c->di, c->order_f, n_feat, c->f_remap, s);
+      e = hipGetLastError();
+    }
+  }
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  for (void* p : {static_cast<void*>(acc), static_cast<void*>(scan), static_cast<void*>(result),
+                  static_cast<void*>(order), static_cast<void*>(owner), static_cast<void*>(queues),
+                  static_cast<void*>(deg), static_cast<void*>(counts)})
+    if (p) (void)hipFree(p);
+  if (e != hipSuccess) {
+    const int st = fail_hip(c, e, "clique cache fill");
+    free_cache(c);
+    launch_init_row_table(c->di, c->g.indptr, c->g.indptr_bytes, V, c->row_tab, s);
+    (void)hipStreamSynchronize(s);
+    (void)hipMemset(c->f_remap, 0xff, sizeof(int32_t) * size_t(V));
+    return st;
+  }
+  c->plan.n_topo = n_topo;
+  c->plan.topo_edges = topo_edges;
+  c->plan.topo_bytes = uint64_t(topo_edges) * 4u + uint64_t(n_topo) * 8u;
+  c->plan.n_feat = fn[k_g];
+  c->plan.feat_bytes = uint64_t(fn[k_g]) * uint64_t(c->row_bytes);
+  c->fc_identity = false;
+  c->clique_k = k_g;
+  for (int32_t g = 0; g <= k_g; ++g) {
+    c->clique_tn[g] = tn[g];
+    c->clique_te[g] = te[g];
+    c->clique_fn[g] = fn[g];
+  }
+  return LGP_OK;
+}
+
+int lgp_get_clique_plan(lgp_ctx* c, int32_t member, lgp_cache_plan* plan) {
+  if (!c) return LGP_EINVAL;
+  if (!plan) return fail(c, LGP_EINVAL, "plan is null");
+  if (c->clique_k == 0) return fail(c, LGP_ESTATE, "no clique cache: call lgp_build_clique_cache first");
+  if (member < 0 || member >= c->clique_k) return fail(c, LGP_EINVAL, "member outside the clique");
+  plan->n_topo = c->clique_tn[member + 1] - c->clique_tn[member];
+  plan->topo_edges = c->clique_te[member + 1] - c->clique_te[member];
+  plan->topo_bytes = uint64_t(plan->topo_edges) * 4u + uint64_t(plan->n_topo) * 8u;
+  plan->n_feat = c->clique_fn[member + 1] - c->clique_fn[member];
+  plan->feat_bytes = uint64_t(plan->n_feat) * uint64_t(c->row_bytes);
+  return LGP_OK;
+}
+
 int lgp_get_cache_plan(lgp_ctx* c, lgp_cache_plan* plan) {
   if (!c) return LGP_EINVAL;
   if (!plan) return fail(c, LGP_EINVAL, "plan is null");
@@ -798,9 +933,9 @@ int lgp_build_blocks(lgp_ctx* c, const int32_t* seeds, int32_t n_seeds, const in
   return LGP_OK;
 }
 
-int lgp_gather_features(lgp_ctx* c, const int32_t* ids, int64_t n_max, const int32_t* n_dev, void* out,
-                        int32_t* stats, void* stream) {
-  if (!c) return LGP_EINVAL;
+// member < 0: plain two-way extraction; member >= 0: three-way, as that member of the clique cache.
+static int gather_core(lgp_ctx* c, int32_t member, const int32_t* ids, int64_t n_max, const int32_t* n_dev, void* out,
+                       int32_t* stats, void* stream) {
   if (n_max < 0 || (n_max > 0 && (!ids || !out))) return fail(c, LGP_EINVAL, "ids / out / n_max");
   if (!c->g.features) return fail(c, LGP_ESTATE, "the graph was created without a feature table");
   if (n_max >= (int64_t(1) << 31)) return fail(c, LGP_EUNSUPPORTED, "more than 2^31 - 1 rows in one call");
@@ -809,42 +944,45 @@ int lgp_gather_features(lgp_ctx* c, const int32_t* ids, int64_t n_max, const int
   if (vec == 0 || c->row_bytes / vec > 4096) return fail(c, LGP_EUNSUPPORTED, "output alignment too small for this row width");
   hipStream_t s = static_cast<hipStream_t>(stream);
   LGP_HIP(c, hipSetDevice(c->di.device));
+  const bool three = member >= 0;
   int32_t* counters = stats ? stats : c->counters;
+  PartLists L = {};
   if (n_max == 0) {
-    launch_partition(c->di, ids, 0, nullptr, c->f_remap, c->g.num_vertices, nullptr, nullptr, nullptr, nullptr,
-                     counters, c->d_err, s);
+    launch_partition(c->di, ids, 0, nullptr, c->f_remap, c->g.num_vertices, L, three ? 3 : 2, 0, 0, counters, c->d_err,
+                     s);
     return LGP_OK;
   }
   const int64_t V = c->g.num_vertices;
   EvPair ev;
-  if (c->plan.n_feat == V) {
+  if (!three && c->plan.n_feat == V) {
     // every row is cached: no partition, the id list is looked up by the gather itself
     ev = prof_begin(c, PK_HIT, s);
     launch_gather_rows(c->di, c->fc, out, c->row_bytes, nullptr, ids, n_max, n_dev, false, s,
                        DirectIds{c->fc_identity ? nullptr : c->f_remap, V, counters, 0, c->d_err});
     prof_end(c, ev, s);
-  } else if (c->plan.n_feat == 0) {
+  } else if (!three && c->plan.n_feat == 0) {
     // nothing is cached: every id is its own source row in CPU memory
     ev = prof_begin(c, PK_MISS, s);
     launch_gather_rows(c->di, c->g.features, out, c->row_bytes, nullptr, ids, n_max, n_dev, true, s,
                        DirectIds{nullptr, V, counters, 1, c->d_err});
     prof_end(c, ev, s);
   } else {
-    if (n_max > c->list_cap) {                     // scratch for the two lists grows on demand
+    if (n_max > c->list_cap) {                     // scratch for the lists grows on demand
       LGP_HIP(c, hipStreamSynchronize(s));
       LGP_HIP(c, hipStreamSynchronize(c->miss_stream));
       if (c->lists) (void)hipFree(c->lists);
       c->lists = nullptr;
       c->list_cap = 0;
-      LGP_HIP(c, dev_alloc(&c->lists, size_t(n_max) * 4));
+      LGP_HIP(c, dev_alloc(&c->lists, size_t(n_max) * 6));
       c->list_cap = n_max;
     }
-    int32_t* hit_row = c->lists;
-    int32_t* hit_src = c->lists + c->list_cap;
-    int32_t* miss_row = c->lists + 2 * c->list_cap;
-    int32_t* miss_src = c->lists + 3 * c->list_cap;
+    for (int l = 0; l < (three ? 3 : 2); ++l) {
+      L.row[l] = c->lists + (2 * l) * c->list_cap;
+      L.src[l] = c->lists + (2 * l + 1) * c->list_cap;
+    }
     ev = prof_begin(c, PK_PARTITION, s);
-    launch_partition(c->di, ids, n_max, n_dev, c->f_remap, V, hit_row, hit_src, miss_row, miss_src, counters,
+    launch_partition(c->di, ids, n_max, n_dev, c->f_remap, V, L, three ? 3 : 2,
+                     three ? int32_t(c->clique_fn[member]) : 0, three ? int32_t(c->clique_fn[member + 1]) : 0, counters,
                      c->d_err, s);
     prof_end(c, ev, s);
     // Hits first (HBM -> HBM, short), then misses (PCIe, long).  With overlap enabled the
@@ -856,10 +994,12 @@ int lgp_gather_features(lgp_ctx* c, const int32_t* ids, int64_t n_max, const int
       LGP_HIP(c, hipStreamWaitEvent(ms, c->ev_fork, 0));
     }
     ev = prof_begin(c, PK_HIT, s);
-    launch_gather_rows(c->di, c->fc, out, c->row_bytes, hit_row, hit_src, n_max, counters, false, s);
+    launch_gather_rows(c->di, c->fc, out, c->row_bytes, L.row[0], L.src[0], n_max, counters, false, s);
+    // rows a peer caches: on this one device a second HBM gather, from the peers' regions
+    if (three) launch_gather_rows(c->di, c->fc, out, c->row_bytes, L.row[2], L.src[2], n_max, counters + 2, false, s);
     prof_end(c, ev, s);
     ev = prof_begin(c, PK_MISS, ms);
-    launch_gather_rows(c->di, c->g.features, out, c->row_bytes, miss_row, miss_src, n_max, counters + 1, true, ms);
+    launch_gather_rows(c->di, c->g.features, out, c->row_bytes, L.row[1], L.src[1], n_max, counters + 1, true, ms);
     prof_end(c, ev, ms);
     if (c->overlap) {
       LGP_HIP(c, hipEventRecord(c->ev_join, ms));
@@ -869,6 +1009,20 @@ int lgp_gather_features(lgp_ctx* c, const int32_t* ids, int64_t n_max, const int
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail_hip(c, e, "gather kernel launch");
   return LGP_OK;
+}
+
+int lgp_gather_features(lgp_ctx* c, const int32_t* ids, int64_t n_max, const int32_t* n_dev, void* out,
+                        int32_t* stats, void* stream) {
+  if (!c) return LGP_EINVAL;
+  return gather_core(c, -1, ids, n_max, n_dev, out, stats, stream);
+}
+
+int lgp_gather_features_clique(lgp_ctx* c, int32_t member, const int32_t* ids, int64_t n_max, const int32_t* n_dev,
+                               void* out, int32_t* stats, void* stream) {
+  if (!c) return LGP_EINVAL;
+  if (c->clique_k == 0) return fail(c, LGP_ESTATE, "no clique cache: call lgp_build_clique_cache first");
+  if (member < 0 || member >= c->clique_k) return fail(c, LGP_EINVAL, "member outside the clique");
+  return gather_core(c, member, ids, n_max, n_dev, out, stats, stream);
 }
 
 int lgp_check(lgp_ctx* c, void* stream) {

@@ -68,11 +68,17 @@ void launch_compact(const DeviceInfo& di, uint64_t* bits, uint64_t* or_into, int
                     int32_t* out, int64_t out_cap, int32_t* n_out, uint32_t* bump, uint32_t* d_err, hipStream_t s);
 
 // ---- gather.hip -----------------------------------------------------------
-// Look up every id in the feature remap and append (row, slot) to the hit list or
-// (row, id) to the miss list.  counters[0] = hits, counters[1] = misses (zeroed here).
+// Look up every id in the feature remap and append (row, slot) to the hit list (list 0) or
+// (row, id) to the miss list (list 1).  With n_lists = 3, hits whose slot lies outside
+// [local_lo, local_hi) go to list 2 instead: rows cached by another member of a clique.
+// counters[l] = entries of list l, l < n_lists (zeroed here).
+struct PartLists {
+  int32_t* row[3];
+  int32_t* src[3];
+};
 void launch_partition(const DeviceInfo& di, const int32_t* ids, int64_t n_max, const int32_t* n_dev,
-                      const int32_t* f_remap, int64_t num_vertices, int32_t* hit_row, int32_t* hit_src,
-                      int32_t* miss_row, int32_t* miss_src, int32_t* counters, uint32_t* d_err, hipStream_t s);
+                      const int32_t* f_remap, int64_t num_vertices, const PartLists& out, int n_lists,
+                      int32_t local_lo, int32_t local_hi, int32_t* counters, uint32_t* d_err, hipStream_t s);
 // "Direct" launches skip the partition: when every row is cached (or none is) the source-row
 // array is the caller's id list itself.
 struct DirectIds {

@@ -19,69 +19,80 @@ namespace {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-__global__ void zero_counters_kernel(int32_t* counters) {
-  if (threadIdx.x < 2) counters[threadIdx.x] = 0;
+__global__ void zero_counters_kernel(int32_t* counters, int n) {
+  if (int(threadIdx.x) < n) counters[threadIdx.x] = 0;
 }
 
-// Each wave looks up 4 x 64 consecutive ids; the workgroup reserves its share of the two
-// lists with ONE atomic per list (the two global counters are the only contended words),
-// then every lane writes its entries at wave-ballot ranks, so both lists stay in
-// ascending row order inside a workgroup.
+// Each wave looks up 4 x 64 consecutive ids; the workgroup reserves its share of every
+// list with ONE atomic per list (the global counters are the only contended words), then
+// every lane writes its entries at wave-ballot ranks, so the lists stay in ascending row
+// order inside a workgroup.  List 0 = hits, list 1 = misses; with NL = 3 a hit whose slot lies
+// outside [local_lo, local_hi) -- another clique member's region of the cache -- goes to list 2.
 constexpr int kPartItems = 4;
+template <int NL>
 __global__ __launch_bounds__(256) void partition_kernel(
     const int32_t* __restrict__ ids, int64_t n_max, const int32_t* __restrict__ n_dev,
-    const int32_t* __restrict__ f_remap, int64_t num_vertices, int32_t* __restrict__ hit_row,
-    int32_t* __restrict__ hit_src, int32_t* __restrict__ miss_row, int32_t* __restrict__ miss_src,
+    const int32_t* __restrict__ f_remap, int64_t num_vertices, PartLists out, int32_t local_lo, int32_t local_hi,
     int32_t* __restrict__ counters, uint32_t* __restrict__ d_err) {
-  __shared__ int wave_hits[4], wave_miss[4], block_base[2];
+  __shared__ int wave_cnt[NL][4], block_base[NL];
   int64_t n = n_dev ? int64_t(*n_dev) : n_max;
   if (n > n_max) n = n_max;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint64_t lower = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
   constexpr int kTile = 256 * kPartItems;
   for (int64_t base = int64_t(blockIdx.x) * kTile; base < n; base += int64_t(gridDim.x) * kTile) {
-    int32_t id[kPartItems], slot[kPartItems];
-    uint64_t hm[kPartItems], mm[kPartItems];
-    int nh = 0, nm = 0;
+    int32_t src[kPartItems];
+    uint64_t mask[NL][kPartItems];
+    int cnt[NL];
+#pragma unroll
+    for (int l = 0; l < NL; ++l) cnt[l] = 0;
 #pragma unroll
     for (int j = 0; j < kPartItems; ++j) {
       const int64_t i = base + wave * (64 * kPartItems) + j * 64 + lane;
       const bool active = i < n;
-      id[j] = active ? ids[i] : 0;
-      const bool ok = active && uint32_t(id[j]) < uint64_t(num_vertices);
+      const int32_t id = active ? ids[i] : 0;
+      const bool ok = active && uint32_t(id) < uint64_t(num_vertices);
       if (active && !ok) atomicOr(d_err, ERR_BAD_ID);
-      slot[j] = ok ? f_remap[id[j]] : -1;
-      hm[j] = __ballot(ok && slot[j] >= 0);
-      mm[j] = __ballot(ok && slot[j] < 0);
-      nh += __popcll(hm[j]);
-      nm += __popcll(mm[j]);
+      const int32_t slot = ok ? f_remap[id] : -1;
+      int which = -1;                               // list of this entry
+      if (ok) which = slot < 0 ? 1 : (NL == 3 && (slot < local_lo || slot >= local_hi)) ? 2 : 0;
+      src[j] = which == 1 ? id : slot;
+#pragma unroll
+      for (int l = 0; l < NL; ++l) {
+        mask[l][j] = __ballot(which == l);
+        cnt[l] += __popcll(mask[l][j]);
+      }
     }
-    if (lane == 0) { wave_hits[wave] = nh; wave_miss[wave] = nm; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      const int th = wave_hits[0] + wave_hits[1] + wave_hits[2] + wave_hits[3];
-      const int tm = wave_miss[0] + wave_miss[1] + wave_miss[2] + wave_miss[3];
-      block_base[0] = th ? atomicAdd(&counters[0], th) : 0;
-      block_base[1] = tm ? atomicAdd(&counters[1], tm) : 0;
+    if (lane == 0) {
+#pragma unroll
+      for (int l = 0; l < NL; ++l) wave_cnt[l][wave] = cnt[l];
     }
     __syncthreads();
-    int hpos = block_base[0], mpos = block_base[1];
-    for (int w = 0; w < wave; ++w) { hpos += wave_hits[w]; mpos += wave_miss[w]; }
+    if (threadIdx.x < NL) {
+      const int l = threadIdx.x;
+      const int t = wave_cnt[l][0] + wave_cnt[l][1] + wave_cnt[l][2] + wave_cnt[l][3];
+      block_base[l] = t ? atomicAdd(&counters[l], t) : 0;
+    }
+    __syncthreads();
+    int pos[NL];
+#pragma unroll
+    for (int l = 0; l < NL; ++l) {
+      pos[l] = block_base[l];
+      for (int w = 0; w < wave; ++w) pos[l] += wave_cnt[l][w];
+    }
 #pragma unroll
     for (int j = 0; j < kPartItems; ++j) {
       const int64_t i = base + wave * (64 * kPartItems) + j * 64 + lane;
       const uint64_t bit = 1ull << lane;
-      if (hm[j] & bit) {
-        const int pos = hpos + __popcll(hm[j] & lower);
-        hit_row[pos] = int32_t(i);
-        hit_src[pos] = slot[j];
-      } else if (mm[j] & bit) {
-        const int pos = mpos + __popcll(mm[j] & lower);
-        miss_row[pos] = int32_t(i);
-        miss_src[pos] = id[j];
+#pragma unroll
+      for (int l = 0; l < NL; ++l) {
+        if (mask[l][j] & bit) {
+          const int at = pos[l] + __popcll(mask[l][j] & lower);
+          out.row[l][at] = int32_t(i);
+          out.src[l][at] = src[j];
+        }
+        pos[l] += __popcll(mask[l][j]);
       }
-      hpos += __popcll(hm[j]);
-      mpos += __popcll(mm[j]);
     }
     __syncthreads();                               // LDS is reused by the next tile
   }
@@ -265,15 +276,20 @@ void launch_group(const DeviceInfo& di, const void* src, void* dst, int64_t row_
 }  // namespace
 
 void launch_partition(const DeviceInfo& di, const int32_t* ids, int64_t n_max, const int32_t* n_dev,
-                      const int32_t* f_remap, int64_t num_vertices, int32_t* hit_row, int32_t* hit_src,
-                      int32_t* miss_row, int32_t* miss_src, int32_t* counters, uint32_t* d_err, hipStream_t s) {
-  hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(64), 0, s, counters);
+                      const int32_t* f_remap, int64_t num_vertices, const PartLists& out, int n_lists,
+                      int32_t local_lo, int32_t local_hi, int32_t* counters, uint32_t* d_err, hipStream_t s) {
+  const bool three = n_lists == 3;
+  hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(64), 0, s, counters, three ? 3 : 2);
   int64_t blocks = (n_max + 256 * kPartItems - 1) / (256 * kPartItems);
   const int64_t full = int64_t(di.num_cus) * 8;
   if (blocks > full) blocks = full;
   if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL(partition_kernel, dim3(unsigned(blocks)), dim3(256), 0, s, ids, n_max, n_dev, f_remap,
-                     num_vertices, hit_row, hit_src, miss_row, miss_src, counters, d_err);
+  if (three)
+    hipLaunchKernelGGL(partition_kernel<3>, dim3(unsigned(blocks)), dim3(256), 0, s, ids, n_max, n_dev, f_remap,
+                       num_vertices, out, local_lo, local_hi, counters, d_err);
+  else
+    hipLaunchKernelGGL(partition_kernel<2>, dim3(unsigned(blocks)), dim3(256), 0, s, ids, n_max, n_dev, f_remap,
+                       num_vertices, out, 0, 0, counters, d_err);
 }
 
 void launch_gather_rows(const DeviceInfo& di, const void* src, void* dst, int64_t row_bytes, const int32_t* row,
