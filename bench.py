@@ -42,6 +42,9 @@ def main() -> int:
     ap.add_argument("--cache-bytes", type=int, default=0,
                     help="one total cache budget B instead of the two ratios; split by --alpha, or by the cost model")
     ap.add_argument("--alpha", type=float, default=None, help="topology share of --cache-bytes (default: cost-model search)")
+    ap.add_argument("--clique", type=int, default=0, metavar="K",
+                    help="also time the step as member 0 of a simulated clique of K GPUs (each member with the "
+                         "workload's cache budgets; secondary figure, replaces the cache at the end of the run)")
     ap.add_argument("--overlap", action="store_true", help="miss gather on a second stream beside the hit gather")
     ap.add_argument("--no-pipeline", action="store_true",
                     help="skip the secondary measurement (sampling of batch i+1 beside feature extraction of batch i)")
@@ -272,6 +275,52 @@ def main() -> int:
         ctx.check()
         del bbuf, blk
 
+    # Secondary figure: the same step as member 0 of a simulated clique of K GPUs.  Every member pre-samples its own
+    # hash share of the tablet and contributes a cache of the workload's budgets; rows a peer caches are read from
+    # the peer's region of this device's HBM, so the time says nothing about a real inter-GPU link -- the split
+    # {own cache, peer's cache, CPU memory} is the result.
+    clique = None
+    if args.clique > 0:
+        K = args.clique
+        HT = torch.empty((K, V), dtype=torch.int32, device="cuda")
+        HF = torch.empty((K, V), dtype=torch.int32, device="cuda")
+        tabs = []
+        for g in range(K):
+            tabs.append(tablet_dev[g::K].contiguous())
+            ctx.build_hotness(tabs[g], spec.batch, spec.fanouts, spec.base_seed + 1000 * g)
+            th, fh = ctx.get_hotness()
+            HT[g].copy_(torch.from_numpy(th.view(np.int32)))
+            HF[g].copy_(torch.from_numpy(fh.view(np.int32)))
+        plans = ctx.build_clique_cache(HT, HF, topo_b, feat_b)
+        del HT, HF
+        my_batches = max(1, tabs[0].numel() // spec.batch)
+        cstats = torch.zeros((args.steps + args.warmup, 3), dtype=torch.int32, device="cuda")
+
+        def cstep(i: int):
+            b = i % my_batches
+            seeds = tabs[0][b * spec.batch:(b + 1) * spec.batch]
+            ctx.sample_khop(seeds, spec.fanouts, spec.base_seed + i, out=buf)
+            ctx.gather_features_clique(0, buf.gather_ids, n_dev=buf.n_gather, out=rows, stats=cstats[i])
+
+        for i in range(args.warmup):
+            cstep(i)
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        for i in range(args.warmup, args.warmup + args.steps):
+            cstep(i)
+        torch.cuda.synchronize()
+        c1 = time.perf_counter()
+        ctx.check()
+        n_seeds = min(spec.batch, tabs[0].numel())
+        tot = cstats[args.warmup:].sum(dim=0).tolist()
+        clique = {"k_g": K, "member": 0, "value": round(args.steps * n_seeds / (c1 - c0), 1), "unit": "seeds/s",
+                  "ms_per_step": round((c1 - c0) * 1e3 / args.steps, 4),
+                  "cached_topo_rows": [p.n_topo for p in plans], "cached_feat_rows": [p.n_feat for p in plans],
+                  "rows_per_step": {"own_cache": round(tot[0] / args.steps, 1), "peer_cache": round(tot[2] / args.steps, 1),
+                                    "cpu_memory": round(tot[1] / args.steps, 1)},
+                  "how": "hash split of the tablet; every member caches the workload's budgets; peers simulated in local HBM"}
+        del tabs, cstats
+
     cpu = None
     cpu_all = None
     if not args.no_cpu_baseline:
@@ -329,7 +378,7 @@ def main() -> int:
                    "batches_in_tablet": n_batches},
         "roofline": roofline, "roofline_pcie": roofline_pcie, "cpu_baseline": cpu, "cpu_baseline_all_cores": cpu_all,
         "pipelined": pipelined, "graph_replay": graph_replay,
-        "graph_constructor_ms": blocks_ms,
+        "graph_constructor_ms": blocks_ms, "clique": clique,
         "per_step": {"gather_rows": round(gathered / args.steps, 1), "hit_rate": round(hit_rows / max(gathered, 1), 4),
                      "ms_sample": round(prof.ms_sample / max(prof.n_sample, 1), 4),
                      "ms_partition": round(prof.ms_partition / max(prof.n_partition, 1), 4),
