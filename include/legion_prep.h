@@ -285,8 +285,11 @@ int lgp_set_overlap(lgp_ctx* ctx, int enable);
 int lgp_check(lgp_ctx* ctx, void* stream);
 
 /* HIP-event timing of the per-batch kernels, recorded on the streams they run on.
- * lgp_get_profile waits for the recorded events, adds them up and resets. */
-int lgp_set_profiling(lgp_ctx* ctx, int enable);
+ * mode 0 = off, 1 = every kernel group of lgp_profile, 2 = only the two row gathers
+ * (hits, misses): an event pair costs a few microseconds of stream time, which shows in
+ * steps that take a fraction of a millisecond.  lgp_get_profile waits for the recorded events, adds
+ * them up and resets. */
+int lgp_set_profiling(lgp_ctx* ctx, int mode);
 int lgp_get_profile(lgp_ctx* ctx, lgp_profile* out);
 
 const char* lgp_strerror(int status);

@@ -434,8 +434,9 @@ class Context:
     def set_overlap(self, enable: bool):
         self._ok(self._L.lgp_set_overlap(self._h, int(bool(enable))))
 
-    def set_profiling(self, enable: bool):
-        self._ok(self._L.lgp_set_profiling(self._h, int(bool(enable))))
+    def set_profiling(self, mode):
+        """False / 0 = off, True / 1 = every kernel group, 2 = the two row gathers only."""
+        self._ok(self._L.lgp_set_profiling(self._h, int(mode)))
 
     def get_profile(self) -> Profile:
         p = Profile()

@@ -71,7 +71,7 @@ struct lgp_ctx {
   hipStream_t miss_stream = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
 
-  bool profiling = false;
+  int profiling = 0;        // 0 off, 1 every per-batch kernel group, 2 the two row gathers only
   bool overlap = false;     // run the miss gather on its own stream beside the hit gather
   std::vector<EvPair> ev_used;
   std::vector<EvPair> ev_free;
@@ -179,7 +179,7 @@ void worst_case(const lgp_ctx* c, int64_t n_seeds, const int32_t* fanouts, int32
 
 EvPair prof_begin(lgp_ctx* c, int kind, hipStream_t s) {
   EvPair p{nullptr, nullptr, kind};
-  if (!c->profiling) return p;
+  if (c->profiling == 0 || (c->profiling == 2 && kind != PK_HIT && kind != PK_MISS)) return p;
   if (!c->ev_free.empty()) {
     p = c->ev_free.back();
     c->ev_free.pop_back();
@@ -1049,7 +1049,7 @@ int lgp_set_overlap(lgp_ctx* c, int enable) {
 
 int lgp_set_profiling(lgp_ctx* c, int enable) {
   if (!c) return LGP_EINVAL;
-  c->profiling = enable != 0;
+  c->profiling = enable == 2 ? 2 : (enable != 0 ? 1 : 0);
   return LGP_OK;
 }
 
