@@ -150,7 +150,7 @@ def test_clique_errors(W):
 
 
 def test_clique_cache_mid_full_size():
-    """Config 2 at full size as a clique of four members: pre-sampling of each member's tablet, the clique plan,
+    """The mid workload (2.4 M vertices, ~62 M edges) at full size as a clique of four members: pre-sampling of each member's tablet, the clique plan,
     cached ids and contents, and three-way extraction of whole batches."""
     from gpu_common import Workload
     Wm = Workload(datagen.MID, device_gen="cuda")
