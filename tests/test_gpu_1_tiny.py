@@ -1,5 +1,7 @@
 """GPU parity on the tiny workload (config 1) and on edge cases: every output of the
 HIP path is compared bit for bit with the CPU oracle on the same seeded inputs."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -483,10 +485,11 @@ def test_row_wider_than_the_limit_is_refused():
     assert e.value.status == -4
 
 
-@pytest.mark.parametrize("case", range(24))
+@pytest.mark.parametrize("case", range(int(os.environ.get("LGP_RANDOM_CASES", "24"))))
 def test_randomized_small_workloads(case):
     """Random small graphs, feature widths, fan-out lists, seed sets and cache splits: sampling, blocks and
-    gathered bytes against the oracle."""
+    gathered bytes against the oracle; then the same graph with the cache of a random clique.
+    LGP_RANDOM_CASES sets the number of cases (default 24)."""
     import oracle
     import paper_2305_16588_amd as lgp
     from gpu_common import assert_batch_equal, assert_blocks_equal
@@ -531,5 +534,30 @@ def test_randomized_small_workloads(case):
     assert rows[:n].cpu().numpy().tobytes() == orc.gather(ref.gather_ids).tobytes()
     n_hit = orc.count_hits(ref.gather_ids, qf, plan.n_feat)
     assert stats.tolist() == [n_hit, n - n_hit]
+    # the cache of a clique of k_g members with random hotness rows (many ties and zeros), three-way extraction
+    k_g = int(rng.integers(1, 9))
+    HT = rng.integers(0, 4, size=(k_g, V)).astype(np.uint32)
+    HF = rng.integers(0, 4, size=(k_g, V)).astype(np.uint32)
+    tb, fb = topo_b // k_g, (feat_b // row_bytes // k_g) * row_bytes + int(rng.integers(0, row_bytes))
+    plans = ctx.build_clique_cache(torch.from_numpy(HT.view(np.int32)).cuda(), torch.from_numpy(HF.view(np.int32)).cuda(),
+                                   tb, fb)
+    topo_ids, feat_ids = orc.clique_plan(HT, HF, tb, fb)
+    assert [p.n_topo for p in plans] == [t.size for t in topo_ids]
+    assert [p.n_feat for p in plans] == [f.size for f in feat_ids]
+    g_topo, g_indptr, g_indices, g_feat, g_rows = ctx.get_cache()
+    all_t, all_f = np.concatenate(topo_ids), np.concatenate(feat_ids)
+    assert (g_topo == all_t).all() and (g_feat == all_f).all()
+    r_indptr, r_indices = orc.fill_topo(all_t, all_t.size)
+    assert (g_indptr == r_indptr).all() and (g_indices == r_indices).all()
+    assert g_rows.tobytes() == orc.fill_feat(all_f, all_f.size).tobytes()
+    ctx.sample_khop(dev, fanouts, seed + 1, out=buf)
+    ref = orc.sample_khop(seeds, fanouts, seed + 1)
+    assert_batch_equal(ref, buf.to_host(dev), f"case {case} with the clique cache")
+    n = ref.gather_ids.size
+    stats3 = torch.zeros(3, dtype=torch.int32, device="cuda")
+    member = int(rng.integers(0, k_g))
+    rows = ctx.gather_features_clique(member, buf.gather_ids, n_dev=buf.n_gather, stats=stats3)
+    assert rows[:n].cpu().numpy().tobytes() == orc.gather(ref.gather_ids).tobytes()
+    assert tuple(stats3.tolist()) == orc.count_three_way(ref.gather_ids, feat_ids, member)
     ctx.check()
     ctx.close()
