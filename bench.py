@@ -236,6 +236,64 @@ def main() -> int:
                      "how": "sample_khop of batch i+1 on a second stream beside gather_features of batch i"}
         del bufs, outs
 
+    # Secondary figure: the whole sampling server of Sec. 5 -- neighbour sampler, graph constructor and feature
+    # extractor per batch -- serial on one stream, and as the two pipelines the section describes: within a batch
+    # the graph constructor beside the feature extractor, across batches the sampling of batch i+1 beside both.
+    server = None
+    if not args.no_pipeline:
+        sA, sB, sC = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+        bufs = [lgp.SampleBuffers(V, spec.batch, spec.fanouts, last_frontier=True) for _ in range(2)]
+        blks = [lgp.BlockBuffers(b) for b in bufs]
+        outs = [rows, torch.empty_like(rows)]
+        ev_s = [torch.cuda.Event(), torch.cuda.Event()]
+        ev_g = [torch.cuda.Event(), torch.cuda.Event()]
+        ev_b = [torch.cuda.Event(), torch.cuda.Event()]
+        sstats = torch.zeros((args.steps + args.warmup, 2), dtype=torch.int32, device="cuda")
+
+        def serial_step(i: int):
+            b = i % full_batches
+            seeds = tablet_dev[b * spec.batch:(b + 1) * spec.batch]
+            ctx.sample_khop(seeds, spec.fanouts, spec.base_seed + i, out=bufs[0])
+            ctx.build_blocks(seeds, spec.fanouts, bufs[0], out=blks[0])
+            ctx.gather_features(bufs[0].gather_ids, n_dev=bufs[0].n_gather, out=outs[0], stats=sstats[i])
+
+        def piped_step(i: int):
+            k = i % 2
+            b = i % full_batches
+            seeds = tablet_dev[b * spec.batch:(b + 1) * spec.batch]
+            if i >= 2:
+                sA.wait_event(ev_g[k])                      # buffer k is free again
+                sA.wait_event(ev_b[k])
+            ctx.sample_khop(seeds, spec.fanouts, spec.base_seed + i, out=bufs[k], stream=sA)
+            ev_s[k].record(sA)
+            sB.wait_event(ev_s[k])
+            sC.wait_event(ev_s[k])
+            ctx.gather_features(bufs[k].gather_ids, n_dev=bufs[k].n_gather, out=outs[k], stats=sstats[i], stream=sB)
+            ev_g[k].record(sB)
+            ctx.build_blocks(seeds, spec.fanouts, bufs[k], out=blks[k], stream=sC)
+            ev_b[k].record(sC)
+
+        times = []
+        for fn in (serial_step, piped_step):
+            torch.cuda.synchronize()
+            for i in range(args.warmup):
+                fn(i)
+            torch.cuda.synchronize()
+            q0 = time.perf_counter()
+            for i in range(args.warmup, args.warmup + args.steps):
+                fn(i)
+            torch.cuda.synchronize()
+            times.append(time.perf_counter() - q0)
+            ctx.check()
+            assert torch.equal(sstats[args.warmup:].cpu(), stats[args.warmup:].cpu()), "sampling-server run diverged"
+        server = {"serial": {"value": round(args.steps * spec.batch / times[0], 1), "unit": "seeds/s",
+                             "ms_per_step": round(times[0] * 1e3 / args.steps, 4)},
+                  "pipelined": {"value": round(args.steps * spec.batch / times[1], 1), "unit": "seeds/s",
+                                "ms_per_step": round(times[1] * 1e3 / args.steps, 4)},
+                  "how": "step = sample_khop + build_blocks + gather_features; pipelined = three streams: build_blocks "
+                         "beside gather_features of the same batch, sample_khop of the next batch beside both"}
+        del bufs, blks, outs
+
     # Secondary figure: the same step captured once into a HIP graph (sampling, dedup, partition, gathers: about a
     # dozen launches) and replayed; seeds change per replay, the rng seed is the captured one.
     graph_replay = None
@@ -386,7 +444,7 @@ def main() -> int:
                    "cached_topo_rows": plan.n_topo, "cached_feat_rows": plan.n_feat, "cache_plan": auto_plan,
                    "batches_in_tablet": n_batches},
         "roofline": roofline, "roofline_pcie": roofline_pcie, "cpu_baseline": cpu, "cpu_baseline_all_cores": cpu_all,
-        "pipelined": pipelined, "graph_replay": graph_replay,
+        "pipelined": pipelined, "sampling_server": server, "graph_replay": graph_replay,
         "graph_constructor_ms": blocks_ms, "clique": clique,
         "per_step": {"gather_rows": round(gathered / args.steps, 1), "hit_rate": round(hit_rows / max(gathered, 1), 4),
                      "ms_sample": round(prof.ms_sample / max(prof.n_sample, 1), 4),

@@ -17,11 +17,14 @@
  * The caller owns every buffer it passes and keeps it alive until the work
  * that uses it has finished (graph arrays: until lgp_destroy).  The library
  * owns the context, the caches, the hotness vectors and its scratch memory.
- * A context is driven from one host thread.  lgp_sample_khop and lgp_gather_features use
- * disjoint scratch memory, so one call of each may be in flight at the same time on two
- * different streams (batch pipelining: sampling of batch i+1 beside feature extraction
- * of batch i, the overlap of Sec. 5); any other pair of calls must be ordered by the
- * caller, e.g. by issuing them on one stream.
+ * A context is driven from one host thread.  lgp_sample_khop, lgp_build_blocks and
+ * lgp_gather_features (or lgp_gather_features_clique) use disjoint scratch memory, so one
+ * call of each may be in flight at the same time on different streams -- the pipelines of
+ * Sec. 5: within a batch the graph constructor beside the feature extractor, across
+ * batches the sampling of batch i+1 beside both (the caller orders what depends on what:
+ * both consumers wait for the sampling of their batch, and a sample buffer is reused only
+ * after its consumers finished).  Any other pair of calls must be ordered by the caller,
+ * e.g. by issuing them on one stream.
  */
 #ifndef LEGION_PREP_H
 #define LEGION_PREP_H

@@ -329,42 +329,54 @@ def test_plan_cache_and_set_hotness():
     assert e.value.status == -2
 
 
-def test_overlap_profiling_and_two_stream_pipelining(W):
-    """The optional modes change scheduling only: same bytes with hit / miss overlap, with event profiling on,
-    and with sampling of the next batch running on a second stream beside the gather of the current one."""
-    from gpu_common import assert_batch_equal
+def test_overlap_profiling_and_three_stream_pipelining(W):
+    """The optional modes change scheduling only: same results with hit / miss overlap, with event profiling on,
+    and with the three operators on three streams -- sampling of the next batch beside the graph constructor and
+    the feature extraction of the current one."""
+    from gpu_common import assert_batch_equal, assert_blocks_equal
     import paper_2305_16588_amd as lgp
     spec = W.spec
     W.ctx.build_hotness(W.tablet_dev, spec.batch, spec.fanouts, spec.base_seed)
     W.ctx.build_cache(*datagen.budgets(spec, W.E))
-    refs = [W.orc.sample_khop(W.batch(b)[0], spec.fanouts, 600 + b) for b in range(4)]
+    refs = [W.orc.sample_khop(W.batch(b)[0], spec.fanouts, 600 + b, blocks=True) for b in range(4)]
     rows_ref = [W.orc.gather(r.gather_ids) for r in refs]
+    sA, sB, sC = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    bufs = [lgp.SampleBuffers(W.V, spec.batch, spec.fanouts, last_frontier=True) for _ in range(2)]
+    blks = [lgp.BlockBuffers(bufs[k]) for k in range(2)]
+    W.ctx.build_blocks(W.batch(0)[1], spec.fanouts, W.ctx.sample_khop(W.batch(0)[1], spec.fanouts, 1, out=bufs[0]),
+                       out=blks[0])                              # first call allocates the constructor's scratch
     W.ctx.set_overlap(True)
     W.ctx.set_profiling(True)
-    sA, sB = torch.cuda.Stream(), torch.cuda.Stream()
-    bufs = [lgp.SampleBuffers(W.V, spec.batch, spec.fanouts) for _ in range(2)]
     outs = [torch.empty((bufs[0].gather_cap, spec.feat_dim), dtype=torch.float32, device="cuda") for _ in range(2)]
     sampled = [torch.cuda.Event() for _ in range(2)]
     gathered = [torch.cuda.Event() for _ in range(2)]
-    copied = []
+    built = [torch.cuda.Event() for _ in range(2)]
+    copied, blocks = [], []
     torch.cuda.synchronize()
     for b in range(4):
         k = b % 2
         if b >= 2:
             sA.wait_event(gathered[k])
+            sA.wait_event(built[k])
         W.ctx.sample_khop(W.batch(b)[1], spec.fanouts, 600 + b, out=bufs[k], stream=sA)
         sampled[k].record(sA)
         sB.wait_event(sampled[k])
+        sC.wait_event(sampled[k])
         W.ctx.gather_features(bufs[k].gather_ids, n_dev=bufs[k].n_gather, out=outs[k], stream=sB)
+        W.ctx.build_blocks(W.batch(b)[1], spec.fanouts, bufs[k], out=blks[k], stream=sC)
         with torch.cuda.stream(sB):                             # snapshot before the buffer is reused
             copied.append((outs[k][:refs[b].gather_ids.size].clone(), bufs[k].gather_ids[:refs[b].gather_ids.size].clone(),
                            bufs[k].n_gather.clone()))
         gathered[k].record(sB)
+        with torch.cuda.stream(sC):
+            blocks.append(blks[k].to_host())
+        built[k].record(sC)
     torch.cuda.synchronize()
     for b in range(4):
         rows, gids, n = copied[b]
         assert int(n.item()) == refs[b].gather_ids.size and (gids.cpu().numpy() == refs[b].gather_ids).all()
         assert rows.cpu().numpy().tobytes() == rows_ref[b].tobytes()
+        assert_blocks_equal(refs[b], blocks[b], f"batch {b}")
     prof = W.ctx.get_profile()
     assert prof.n_sample == 4 and prof.n_partition == 4 and prof.n_hit == 4 and prof.n_miss == 4
     assert prof.ms_sample > 0 and prof.ms_hit > 0 and prof.ms_miss > 0
