@@ -257,8 +257,9 @@ int lgp_sample_khop(lgp_ctx* ctx, const int32_t* seeds, int32_t n_seeds, const i
  * and `sampled`, with sampled->frontier[n_hops] given) and writes, per hop h, a bipartite
  * block in CSR form whose destinations are frontier h and whose sources are frontier h+1,
  * plus for every frontier the rows of its vertices in the extracted feature matrix.
- * Everything is read from device memory; no host synchronisation.  The first call
- * allocates a V-entry lookup table and a small scan scratch (and synchronises once). */
+ * Everything is read from device memory; no host synchronisation.  The first call (and a
+ * later one with more hops) allocates n_hops + 1 lookup tables of V 4-byte entries and a
+ * small scan scratch, and synchronises once. */
 int lgp_build_blocks(lgp_ctx* ctx, const int32_t* seeds, int32_t n_seeds, const int32_t* fanouts, int32_t n_hops,
                      const lgp_sample_out* sampled, const lgp_blocks_out* out, void* stream);
 

@@ -57,7 +57,8 @@ struct lgp_ctx {
   int64_t list_cap = 0;
 
   // graph-constructor scratch
-  int32_t* pos_table = nullptr;   // V entries: position of a vertex in the frontier scattered last
+  int32_t* pos_table = nullptr;   // pos_tables tables of V entries: position of a vertex in one list of the batch
+  int32_t pos_tables = 0;
   int64_t* tile_sums = nullptr;
   int64_t tile_cap = 0;
 
@@ -883,7 +884,6 @@ int lgp_build_blocks(lgp_ctx* c, const int32_t* seeds, int32_t n_seeds, const in
   if (!sampled->n_frontier || !sampled->n_gather) return fail(c, LGP_EINVAL, "sampled has null count pointers");
   int64_t need[LGP_MAX_HOPS + 1], gather_need;
   worst_case(c, n_seeds, fanouts, n_hops, need, &gather_need);
-  int64_t max_cap = 0;
   for (int h = 0; h <= n_hops; ++h) {
     if (h < n_hops && !out->blk_indptr[h]) return fail(c, LGP_EINVAL, "out->blk_indptr[h] is null");
     if (need[h] == 0) continue;
@@ -893,41 +893,52 @@ int lgp_build_blocks(lgp_ctx* c, const int32_t* seeds, int32_t n_seeds, const in
     if (!out->feat_row[h]) return fail(c, LGP_EINVAL, "out->feat_row[h] is null");
     if (h < n_hops && (!sampled->nbr[h] || !sampled->cnt[h] || !out->blk_indptr[h] || !out->blk_src[h]))
       return fail(c, LGP_EINVAL, "a hop buffer is null");
-    max_cap = std::max(max_cap, sampled->cap[h]);
   }
   if (gather_need > 0 && !sampled->gather_ids) return fail(c, LGP_EINVAL, "sampled->gather_ids is null");
   hipStream_t s = static_cast<hipStream_t>(stream);
   LGP_HIP(c, hipSetDevice(c->di.device));
-  const int64_t tiles = max_cap / kScanTile + 1;
-  if (!c->pos_table || c->tile_cap < tiles) {
-    LGP_HIP(c, hipStreamSynchronize(s));
-    if (!c->pos_table) LGP_HIP(c, dev_alloc(&c->pos_table, size_t(c->g.num_vertices)));
-    if (c->tile_sums) (void)hipFree(c->tile_sums);
-    c->tile_sums = nullptr;
-    c->tile_cap = 0;
-    LGP_HIP(c, dev_alloc(&c->tile_sums, size_t(tiles)));
-    c->tile_cap = tiles;
-  }
-  const int64_t V = c->g.num_vertices;
-  // rows of every frontier in the extracted feature matrix
-  launch_scatter_pos(c->di, sampled->gather_ids, sampled->n_gather, sampled->gather_cap, c->pos_table, s);
+  BlocksArgs a = {};
+  a.n_hops = n_hops;
+  a.num_vertices = c->g.num_vertices;
+  a.n_frontier = sampled->n_frontier;
+  a.gather_ids = sampled->gather_ids;
+  a.n_gather = sampled->n_gather;
+  a.gather_cap = gather_need > 0 ? sampled->gather_cap : 0;
+  int64_t tiles = 0;
   for (int h = 0; h <= n_hops; ++h) {
-    if (need[h] == 0) continue;
-    const int32_t* fr = h == 0 ? seeds : sampled->frontier[h];
-    launch_lookup_pos(c->di, fr, sampled->n_frontier + h, sampled->cap[h], c->pos_table, V, out->feat_row[h], s);
+    a.frontier[h] = h == 0 ? seeds : sampled->frontier[h];
+    a.cap[h] = need[h] ? sampled->cap[h] : 0;
+    a.feat_row[h] = out->feat_row[h];
+    if (h == n_hops) break;
+    a.nbr[h] = sampled->nbr[h];
+    a.cnt[h] = sampled->cnt[h];
+    a.fanout[h] = fanouts[h];
+    a.blk_indptr[h] = out->blk_indptr[h];
+    a.blk_src[h] = out->blk_src[h];
+    a.tile_base[h] = tiles;
+    tiles += a.cap[h] / kScanTile + 1;
   }
-  // one bipartite block per hop: destinations = frontier h, sources = frontier h + 1
-  for (int h = 0; h < n_hops; ++h) {
-    // an empty frontier still gets its one-entry offset array
-    launch_counts_to_offsets(c->di, sampled->cnt[h], sampled->n_frontier + h, need[h] ? sampled->cap[h] : 0,
-                             c->tile_sums, out->blk_indptr[h], s);
-    if (need[h] == 0) continue;
-    if (need[h + 1] > 0)
-      launch_scatter_pos(c->di, sampled->frontier[h + 1], sampled->n_frontier + h + 1, sampled->cap[h + 1],
-                         c->pos_table, s);
-    launch_relabel(c->di, sampled->nbr[h], out->blk_indptr[h], fanouts[h], sampled->n_frontier + h, sampled->cap[h],
-                   c->pos_table, out->blk_src[h], s);
+  // scratch: one position table per list (the extracted ids and every frontier after the seeds) and the scan tiles
+  if (c->pos_tables < n_hops + 1 || c->tile_cap < tiles) {
+    LGP_HIP(c, hipStreamSynchronize(s));
+    if (c->pos_tables < n_hops + 1) {
+      if (c->pos_table) (void)hipFree(c->pos_table);
+      c->pos_table = nullptr;
+      c->pos_tables = 0;
+      LGP_HIP(c, dev_alloc(&c->pos_table, size_t(n_hops + 1) * size_t(c->g.num_vertices)));
+      c->pos_tables = n_hops + 1;
+    }
+    if (c->tile_cap < tiles) {
+      if (c->tile_sums) (void)hipFree(c->tile_sums);
+      c->tile_sums = nullptr;
+      c->tile_cap = 0;
+      LGP_HIP(c, dev_alloc(&c->tile_sums, size_t(tiles)));
+      c->tile_cap = tiles;
+    }
   }
+  a.table = c->pos_table;
+  a.tile_sums = c->tile_sums;
+  launch_build_blocks(c->di, a, s);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail_hip(c, e, "graph constructor launch");
   return LGP_OK;

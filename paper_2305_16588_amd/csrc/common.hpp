@@ -98,18 +98,28 @@ void launch_gather_rows(const DeviceInfo& di, const void* src, void* dst, int64_
 
 // ---- blocks.hip -----------------------------------------------------------
 constexpr int kScanTile = 1024;   // elements per workgroup of the counts -> offsets scan
-// table[ids[j]] = j for j < *n_dev.
-void launch_scatter_pos(const DeviceInfo& di, const int32_t* ids, const int32_t* n_dev, int64_t cap, int32_t* table,
-                        hipStream_t s);
-// out[i] = table[ids[i]] for i < *n_dev (-1 for an id outside [0, V)).
-void launch_lookup_pos(const DeviceInfo& di, const int32_t* ids, const int32_t* n_dev, int64_t cap,
-                       const int32_t* table, int64_t num_vertices, int32_t* out, hipStream_t s);
-// indptr[i] = cnt[0] + ... + cnt[i-1] for i <= *n_dev (64-bit sums); tile_sums holds ceil(cap / kScanTile) entries.
-void launch_counts_to_offsets(const DeviceInfo& di, const int32_t* cnt, const int32_t* n_dev, int64_t cap,
-                              int64_t* tile_sums, int64_t* indptr, hipStream_t s);
-// blk_src[indptr[i] + k] = table[nbr[i, k]] for every valid sample.
-void launch_relabel(const DeviceInfo& di, const int32_t* nbr, const int64_t* indptr, int32_t fanout,
-                    const int32_t* n_dev, int64_t cap, const int32_t* table, int32_t* blk_src, hipStream_t s);
+// Everything one graph-constructor call reads and writes.  cap[h] = 0 marks a frontier that
+// is empty in the worst case: its lists are not touched, its hop still gets blk_indptr[h][0] = 0.
+struct BlocksArgs {
+  int32_t n_hops;
+  int64_t num_vertices;
+  const int32_t* frontier[LGP_MAX_HOPS + 1];   // [0] = the seeds
+  const int32_t* n_frontier;                   // device int32[n_hops + 1]
+  int64_t cap[LGP_MAX_HOPS + 1];
+  const int32_t* gather_ids;
+  const int32_t* n_gather;
+  int64_t gather_cap;
+  const int32_t* nbr[LGP_MAX_HOPS];
+  const int32_t* cnt[LGP_MAX_HOPS];
+  int32_t fanout[LGP_MAX_HOPS];
+  int64_t* blk_indptr[LGP_MAX_HOPS];
+  int32_t* blk_src[LGP_MAX_HOPS];
+  int32_t* feat_row[LGP_MAX_HOPS + 1];
+  int32_t* table;                              // n_hops + 1 tables of num_vertices entries each
+  int64_t* tile_sums;                          // hop h owns cap[h] / kScanTile + 1 entries from tile_base[h]
+  int64_t tile_base[LGP_MAX_HOPS];
+};
+void launch_build_blocks(const DeviceInfo& di, const BlocksArgs& a, hipStream_t s);
 
 // ---- cache.hip ------------------------------------------------------------
 struct CachePlan {
