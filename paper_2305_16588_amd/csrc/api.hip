@@ -188,6 +188,7 @@ EvPair prof_begin(lgp_ctx* c, int kind, hipStream_t s) {
   } else {
     if (hipEventCreate(&p.a) != hipSuccess || hipEventCreate(&p.b) != hipSuccess) {
       (void)hipGetLastError();
+      if (p.a) (void)hipEventDestroy(p.a);
       p.a = p.b = nullptr;
       return p;
     }
