@@ -291,8 +291,10 @@ int lgp_check(lgp_ctx* ctx, void* stream);
 
 /* HIP-event timing of the per-batch kernels, recorded on the streams they run on.
  * mode 0 = off, 1 = every kernel group of lgp_profile, 2 = only the two row gathers
- * (hits, misses): an event pair costs a few microseconds of stream time, which shows in
- * steps that take a fraction of a millisecond.  lgp_get_profile waits for the recorded events, adds
+ * (hits, misses).  The gather launches record their own start and stop times; the groups
+ * of several launches (sampling, partition) are bracketed by two recorded events, each of
+ * which costs a few microseconds of stream time -- visible in steps that take a fraction of
+ * a millisecond, hence mode 2.  lgp_get_profile waits for the recorded events, adds
  * them up and resets. */
 int lgp_set_profiling(lgp_ctx* ctx, int mode);
 int lgp_get_profile(lgp_ctx* ctx, lgp_profile* out);

@@ -178,23 +178,31 @@ void worst_case(const lgp_ctx* c, int64_t n_seeds, const int32_t* fanouts, int32
   *gather_need = std::min(V, total);
 }
 
-EvPair prof_begin(lgp_ctx* c, int kind, hipStream_t s) {
+// A pair of events for a launch that records its own start and stop times (nothing is enqueued here).
+EvPair prof_pair(lgp_ctx* c, int kind) {
   EvPair p{nullptr, nullptr, kind};
   if (c->profiling == 0 || (c->profiling == 2 && kind != PK_HIT && kind != PK_MISS)) return p;
   if (!c->ev_free.empty()) {
     p = c->ev_free.back();
     c->ev_free.pop_back();
     p.kind = kind;
-  } else {
-    if (hipEventCreate(&p.a) != hipSuccess || hipEventCreate(&p.b) != hipSuccess) {
-      (void)hipGetLastError();
-      if (p.a) (void)hipEventDestroy(p.a);
-      p.a = p.b = nullptr;
-      return p;
-    }
+  } else if (hipEventCreate(&p.a) != hipSuccess || hipEventCreate(&p.b) != hipSuccess) {
+    (void)hipGetLastError();
+    if (p.a) (void)hipEventDestroy(p.a);
+    p.a = p.b = nullptr;
   }
-  (void)hipEventRecord(p.a, s);
   return p;
+}
+
+// Bracket a group of launches: a is recorded now, b by prof_end.
+EvPair prof_begin(lgp_ctx* c, int kind, hipStream_t s) {
+  EvPair p = prof_pair(c, kind);
+  if (p.a) (void)hipEventRecord(p.a, s);
+  return p;
+}
+
+void prof_keep(lgp_ctx* c, const EvPair& p) {
+  if (p.a) c->ev_used.push_back(p);
 }
 
 void prof_end(lgp_ctx* c, EvPair& p, hipStream_t s) {
@@ -968,16 +976,16 @@ static int gather_core(lgp_ctx* c, int32_t member, const int32_t* ids, int64_t n
   EvPair ev;
   if (!three && c->plan.n_feat == V) {
     // every row is cached: no partition, the id list is looked up by the gather itself
-    ev = prof_begin(c, PK_HIT, s);
+    ev = prof_pair(c, PK_HIT);
     launch_gather_rows(c->di, c->fc, out, c->row_bytes, nullptr, ids, n_max, n_dev, false, s,
-                       DirectIds{c->fc_identity ? nullptr : c->f_remap, V, counters, 0, c->d_err});
-    prof_end(c, ev, s);
+                       DirectIds{c->fc_identity ? nullptr : c->f_remap, V, counters, 0, c->d_err}, ev.a, ev.b);
+    prof_keep(c, ev);
   } else if (!three && c->plan.n_feat == 0) {
     // nothing is cached: every id is its own source row in CPU memory
-    ev = prof_begin(c, PK_MISS, s);
+    ev = prof_pair(c, PK_MISS);
     launch_gather_rows(c->di, c->g.features, out, c->row_bytes, nullptr, ids, n_max, n_dev, true, s,
-                       DirectIds{nullptr, V, counters, 1, c->d_err});
-    prof_end(c, ev, s);
+                       DirectIds{nullptr, V, counters, 1, c->d_err}, ev.a, ev.b);
+    prof_keep(c, ev);
   } else {
     if (n_max > c->list_cap) {                     // scratch for the lists grows on demand
       LGP_HIP(c, hipStreamSynchronize(s));
@@ -1005,14 +1013,21 @@ static int gather_core(lgp_ctx* c, int32_t member, const int32_t* ids, int64_t n
       LGP_HIP(c, hipEventRecord(c->ev_fork, s));
       LGP_HIP(c, hipStreamWaitEvent(ms, c->ev_fork, 0));
     }
-    ev = prof_begin(c, PK_HIT, s);
-    launch_gather_rows(c->di, c->fc, out, c->row_bytes, L.row[0], L.src[0], n_max, counters, false, s);
-    // rows a peer caches: on this one device a second HBM gather, from the peers' regions
-    if (three) launch_gather_rows(c->di, c->fc, out, c->row_bytes, L.row[2], L.src[2], n_max, counters + 2, false, s);
-    prof_end(c, ev, s);
-    ev = prof_begin(c, PK_MISS, ms);
-    launch_gather_rows(c->di, c->g.features, out, c->row_bytes, L.row[1], L.src[1], n_max, counters + 1, true, ms);
-    prof_end(c, ev, ms);
+    const DirectIds listed{nullptr, 0, nullptr, 0, nullptr};
+    ev = prof_pair(c, PK_HIT);
+    launch_gather_rows(c->di, c->fc, out, c->row_bytes, L.row[0], L.src[0], n_max, counters, false, s, listed, ev.a,
+                       ev.b);
+    prof_keep(c, ev);
+    if (three) {   // rows a peer caches: on this one device a second HBM gather, from the peers' regions
+      ev = prof_pair(c, PK_HIT);
+      launch_gather_rows(c->di, c->fc, out, c->row_bytes, L.row[2], L.src[2], n_max, counters + 2, false, s, listed,
+                         ev.a, ev.b);
+      prof_keep(c, ev);
+    }
+    ev = prof_pair(c, PK_MISS);
+    launch_gather_rows(c->di, c->g.features, out, c->row_bytes, L.row[1], L.src[1], n_max, counters + 1, true, ms,
+                       listed, ev.a, ev.b);
+    prof_keep(c, ev);
     if (c->overlap) {
       LGP_HIP(c, hipEventRecord(c->ev_join, ms));
       LGP_HIP(c, hipStreamWaitEvent(s, c->ev_join, 0));

@@ -11,6 +11,8 @@
 // need to sit in LDS because a chunk is loaded and stored by the same lane.
 #include "common.hpp"
 
+#include <hip/hip_ext.h>
+
 #include <algorithm>
 
 namespace lgp {
@@ -211,9 +213,23 @@ inline unsigned blocks_for(int64_t work_blocks, int64_t limit) {
   return unsigned(b < 1 ? 1 : b);
 }
 
+// Where a gather kernel is launched: on stream s, and -- when a and b are given -- with its own start
+// and stop times recorded into those two events (hipExtLaunchKernelGGL), which costs no extra packets
+// on the stream, unlike a pair of hipEventRecord calls around the launch.
+struct Where {
+  hipStream_t s;
+  hipEvent_t a, b;
+};
+
+template <typename K, typename... Args>
+void launch_on(const Where& w, K kernel, unsigned blocks, Args... args) {
+  if (w.a && w.b) hipExtLaunchKernelGGL(kernel, dim3(blocks), dim3(256), 0, w.s, w.a, w.b, 0, args...);
+  else hipLaunchKernelGGL(kernel, dim3(blocks), dim3(256), 0, w.s, args...);
+}
+
 template <typename VecT>
 void launch_flat(const DeviceInfo& di, const void* src, void* dst, int64_t row_bytes, const int32_t* row,
-                 const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, const DirectIds& dir, hipStream_t s) {
+                 const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, const DirectIds& dir, const Where& s) {
   const uint32_t cpr = uint32_t(row_bytes / int64_t(sizeof(VecT)));
   const uint64_t inv = (uint64_t(1) << 32) / cpr + 1;          // exact for flat < 64 * cpr, cpr <= 4096
   const unsigned blocks = blocks_for((n_max + 255) / 256, int64_t(di.num_cus) * 8);
@@ -221,23 +237,23 @@ void launch_flat(const DeviceInfo& di, const void* src, void* dst, int64_t row_b
   // rows).  Rows that straddle lines share their boundary lines between consecutive load
   // instructions, and L2 has to merge those (non-temporal loads cost 7 % on 400-B rows).
   if (row_bytes % 128 == 0)
-    hipLaunchKernelGGL((gather_rows_flat_kernel<VecT, 4, true>), dim3(blocks), dim3(256), 0, s,
+    launch_on(s, gather_rows_flat_kernel<VecT, 4, true>, blocks,
                        static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, inv, row, srcrow, n_max, n_dev, dir);
   else
-    hipLaunchKernelGGL((gather_rows_flat_kernel<VecT, 4, false>), dim3(blocks), dim3(256), 0, s,
+    launch_on(s, gather_rows_flat_kernel<VecT, 4, false>, blocks,
                        static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, inv, row, srcrow, n_max, n_dev, dir);
 }
 
 template <typename VecT, int G>
 void launch_group_g(const DeviceInfo& di, const void* src, void* dst, uint32_t cpr, const int32_t* row,
-                    const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, const DirectIds& dir, hipStream_t s) {
+                    const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, const DirectIds& dir, const Where& s) {
   constexpr int U = 4;
   // PCIe needs far fewer waves than HBM to stay saturated (bandwidth x latency is ~150 KB): one
   // workgroup per four CUs holds ~1 MB of reads in flight, and measured rates FALL with wider grids
   // (400-B rows 44.9 -> 44.0 GB/s, 2-KiB rows 57.5 -> 55.7 GB/s from 64 to 512 workgroups), because the
   // excess requests only queue up in front of the link.
   const unsigned blocks = blocks_for((n_max + (256 / G) * U - 1) / ((256 / G) * U), std::max(1, di.num_cus / 4));
-  hipLaunchKernelGGL((gather_rows_group_kernel<VecT, G, U, false>), dim3(blocks), dim3(256), 0, s,
+  launch_on(s, gather_rows_group_kernel<VecT, G, U, false>, blocks,
                      static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, row, srcrow, n_max, n_dev, dir);
 }
 
@@ -247,15 +263,15 @@ void launch_group_g(const DeviceInfo& di, const void* src, void* dst, uint32_t c
 template <typename VecT, int G>
 void launch_group_hbm_g(const DeviceInfo& di, const void* src, void* dst, uint32_t cpr, const int32_t* row,
                         const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, const DirectIds& dir,
-                        hipStream_t s) {
+                        const Where& s) {
   const unsigned blocks = blocks_for((n_max + 256 / G - 1) / (256 / G), int64_t(di.num_cus) * 8);
-  hipLaunchKernelGGL((gather_rows_group_kernel<VecT, G, 1, true>), dim3(blocks), dim3(256), 0, s,
+  launch_on(s, gather_rows_group_kernel<VecT, G, 1, true>, blocks,
                      static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, row, srcrow, n_max, n_dev, dir);
 }
 
 template <typename VecT>
 void launch_group_hbm(const DeviceInfo& di, const void* src, void* dst, uint32_t cpr, const int32_t* row,
-                      const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, const DirectIds& dir, hipStream_t s) {
+                      const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, const DirectIds& dir, const Where& s) {
   if (cpr <= 4) launch_group_hbm_g<VecT, 4>(di, src, dst, cpr, row, srcrow, n_max, n_dev, dir, s);
   else if (cpr <= 8) launch_group_hbm_g<VecT, 8>(di, src, dst, cpr, row, srcrow, n_max, n_dev, dir, s);
   else if (cpr <= 16) launch_group_hbm_g<VecT, 16>(di, src, dst, cpr, row, srcrow, n_max, n_dev, dir, s);
@@ -264,7 +280,7 @@ void launch_group_hbm(const DeviceInfo& di, const void* src, void* dst, uint32_t
 
 template <typename VecT>
 void launch_group(const DeviceInfo& di, const void* src, void* dst, int64_t row_bytes, const int32_t* row,
-                  const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, const DirectIds& dir, hipStream_t s) {
+                  const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, const DirectIds& dir, const Where& s) {
   const uint32_t cpr = uint32_t(row_bytes / int64_t(sizeof(VecT)));
   if (cpr <= 4) launch_group_g<VecT, 4>(di, src, dst, cpr, row, srcrow, n_max, n_dev, dir, s);
   else if (cpr <= 8) launch_group_g<VecT, 8>(di, src, dst, cpr, row, srcrow, n_max, n_dev, dir, s);
@@ -293,9 +309,10 @@ void launch_partition(const DeviceInfo& di, const int32_t* ids, int64_t n_max, c
 }
 
 void launch_gather_rows(const DeviceInfo& di, const void* src, void* dst, int64_t row_bytes, const int32_t* row,
-                        const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, bool streaming, hipStream_t s,
-                        const DirectIds& dir) {
+                        const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, bool streaming, hipStream_t stream,
+                        const DirectIds& dir, hipEvent_t ev_start, hipEvent_t ev_stop) {
   if (n_max <= 0) return;
+  const Where s{stream, ev_start, ev_stop};
   const uintptr_t align = uintptr_t(src) | uintptr_t(dst) | uintptr_t(row_bytes);
 #define LGP_ROWS(VecT)                                                                        \
   do {                                                                                        \
