@@ -182,15 +182,27 @@ __global__ __launch_bounds__(256) void gather_rows_group_kernel(const VecT* __re
   const uint32_t sub = threadIdx.x % G;
   const int64_t group = (int64_t(blockIdx.x) * 256 + threadIdx.x) / G;
   const int64_t n_groups = int64_t(gridDim.x) * (256 / G);
-  for (int64_t e0 = group * UNROLL; e0 < n; e0 += n_groups * UNROLL) {
+  // The list entries of the next pass are loaded before the rows of this one, so that a pass waits
+  // for one round trip to memory (its rows), not two in a row (entries, then rows).
+  int32_t next_src[UNROLL], next_row[UNROLL];
+  const int64_t first = group * UNROLL;
+#pragma unroll
+  for (int u = 0; u < UNROLL; ++u) {
+    const int64_t e = first + u;
+    next_src[u] = e < n ? (srcrow ? srcrow[e] : int32_t(e)) : 0;
+    next_row[u] = e < n ? (row ? row[e] : int32_t(e)) : 0;
+  }
+  for (int64_t e0 = first; e0 < n; e0 += n_groups * UNROLL) {
     int64_t so[UNROLL], dof[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
-      const int64_t e = e0 + u;
-      const bool ok = e < n;
-      const int32_t sr = direct_source(dir, ok ? (srcrow ? srcrow[e] : int32_t(e)) : 0, ok);
+      const bool ok = e0 + u < n;
+      const int32_t sr = direct_source(dir, next_src[u], ok);
       so[u] = sr >= 0 ? int64_t(sr) * cpr : -1;
-      dof[u] = ok ? int64_t(row ? row[e] : int32_t(e)) * cpr : 0;
+      dof[u] = int64_t(next_row[u]) * cpr;
+      const int64_t e = e0 + n_groups * UNROLL + u;
+      next_src[u] = e < n ? (srcrow ? srcrow[e] : int32_t(e)) : 0;
+      next_row[u] = e < n ? (row ? row[e] : int32_t(e)) : 0;
     }
     for (uint32_t c0 = 0; c0 < cpr; c0 += G) {
       const uint32_t col = c0 + sub;
