@@ -4,6 +4,7 @@
 
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -377,7 +378,12 @@ int lgp_create(const lgp_graph* g, int device, lgp_ctx** out) {
     if (vec == 0 || c->row_bytes / vec > 4096) return bail(LGP_EUNSUPPORTED);
   }
   const int64_t V = g->num_vertices;
-  c->n_chunks = (V + kChunkBits - 1) / kChunkBits;
+  // Small graphs get a sparser dedup bitmap (vertex v = bit v << spread_shift, up to 2^24 bits): the
+  // sampler's atomics on a bitmap of a few cache lines serialise on those lines.
+  c->di.spread_shift = 0;
+  while (c->di.spread_shift < kMaxSpreadShift && (V << (c->di.spread_shift + 1)) <= kSpreadTargetBits)
+    ++c->di.spread_shift;
+  c->n_chunks = ((V << c->di.spread_shift) + kChunkBits - 1) / kChunkBits;
   const size_t words = size_t(c->n_chunks) * size_t(kChunkWords);
   hipError_t e = hipSuccess;
   auto step = [&](hipError_t r) {

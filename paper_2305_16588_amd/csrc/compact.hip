@@ -53,7 +53,7 @@ template <bool WITH_OUT>
 __global__ __launch_bounds__(kCompactThreads) void emit_bits_kernel(
     uint64_t* __restrict__ bits, uint64_t* __restrict__ or_into, const int32_t* __restrict__ chunk_counts,
     int32_t* __restrict__ out, int64_t out_cap, int32_t* __restrict__ n_out, uint32_t* __restrict__ bump,
-    uint32_t* __restrict__ d_err) {
+    uint32_t* __restrict__ d_err, int shift) {
   const int64_t word0 = int64_t(blockIdx.x) * kChunkWords + int64_t(threadIdx.x) * kWordsPerThread;
   uint64_t w[kWordsPerThread];
   int c = 0;
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(kCompactThreads) void emit_bits_kernel(
     const int64_t id0 = (word0 + q) * 64;
     while (x) {
       const int b = __ffsll((unsigned long long)x) - 1;
-      const int32_t id = int32_t(id0 + b);
+      const int32_t id = int32_t((id0 + b) >> shift);
       if (WITH_OUT) {
         if (pos < out_cap) out[pos] = id;
         ++pos;
@@ -101,14 +101,13 @@ __global__ __launch_bounds__(kCompactThreads) void emit_bits_kernel(
 
 void launch_compact(const DeviceInfo& di, uint64_t* bits, uint64_t* or_into, int64_t n_chunks, int32_t* chunk_counts,
                     int32_t* out, int64_t out_cap, int32_t* n_out, uint32_t* bump, uint32_t* d_err, hipStream_t s) {
-  (void)di;
   if (n_out) {
     hipLaunchKernelGGL(count_bits_kernel, dim3(unsigned(n_chunks)), dim3(kCompactThreads), 0, s, bits, chunk_counts);
     hipLaunchKernelGGL((emit_bits_kernel<true>), dim3(unsigned(n_chunks)), dim3(kCompactThreads), 0, s, bits, or_into,
-                       chunk_counts, out, out_cap, n_out, bump, d_err);
+                       chunk_counts, out, out_cap, n_out, bump, d_err, di.spread_shift);
   } else {
     hipLaunchKernelGGL((emit_bits_kernel<false>), dim3(unsigned(n_chunks)), dim3(kCompactThreads), 0, s, bits,
-                       or_into, chunk_counts, out, out_cap, n_out, bump, d_err);
+                       or_into, chunk_counts, out, out_cap, n_out, bump, d_err, di.spread_shift);
   }
 }
 

@@ -19,7 +19,7 @@ __global__ __launch_bounds__(256) void sample_hop_kernel(
     const int32_t* __restrict__ t_indices, int64_t num_vertices,
     const int32_t* __restrict__ frontier, int32_t* __restrict__ n_frontier, int64_t cap, int32_t f, int32_t hop,
     uint32_t k0, uint32_t k1, int32_t* __restrict__ nbr, int32_t* __restrict__ cnt, uint32_t* __restrict__ mark_bits,
-    uint32_t* __restrict__ self_bits, uint32_t* __restrict__ topo_hot, uint32_t* __restrict__ d_err) {
+    uint32_t* __restrict__ self_bits, uint32_t* __restrict__ topo_hot, uint32_t* __restrict__ d_err, int shift) {
   constexpr int G = 256 / P;                      // vertices per workgroup pass
   // self_bits != nullptr: this is the first hop; the frontier is the caller's seed list of `cap`
   // ids, whose size is published here and whose members are marked in the gather set.
@@ -86,13 +86,17 @@ __global__ __launch_bounds__(256) void sample_hop_kernel(
           atomicOr(d_err, ERR_BAD_ID);
           u = -1;
         } else {
-          atomicOr(&mark_bits[uint32_t(u) >> 5], 1u << (uint32_t(u) & 31u));
+          const uint64_t b = uint64_t(uint32_t(u)) << shift;
+          atomicOr(&mark_bits[b >> 5], 1u << (uint32_t(b) & 31u));
         }
       }
       if (nbr) nbr[g * f + i] = u;
     }
     if (active && i == 0) {
-      if (self_bits && !bad) atomicOr(&self_bits[uint32_t(v) >> 5], 1u << (uint32_t(v) & 31u));
+      if (self_bits && !bad) {
+        const uint64_t b = uint64_t(uint32_t(v)) << shift;
+        atomicOr(&self_bits[b >> 5], 1u << (uint32_t(b) & 31u));
+      }
       const int32_t c = d < f ? d : f;
       if (cnt) cnt[g] = c;
       if (topo_hot && c > 0) atomicAdd(&topo_hot[v], uint32_t(c));
@@ -124,7 +128,7 @@ void launch_one(const DeviceInfo& di, const TopoView& tv, const int32_t* frontie
   hipLaunchKernelGGL((sample_hop_kernel<IdxT, P>), dim3(unsigned(blocks)), dim3(256), 0, s,
                      tv.row_tab, static_cast<const IdxT*>(tv.h_indptr), tv.h_indices, tv.t_indices,
                      tv.num_vertices, frontier, n_frontier, cap, f, hop, uint32_t(seed), uint32_t(seed >> 32), nbr,
-                     cnt, mark_bits, self_bits, topo_hot, d_err);
+                     cnt, mark_bits, self_bits, topo_hot, d_err, di.spread_shift);
 }
 
 template <typename IdxT>
