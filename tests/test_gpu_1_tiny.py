@@ -383,6 +383,18 @@ def test_overlap_profiling_and_three_stream_pipelining(W):
     W.ctx.set_overlap(False)
     W.ctx.set_profiling(False)
     assert W.ctx.get_profile().n_sample == 0                     # reading resets the accumulators
+    # mode 2 times the two row gathers only; the launches carry their own start / stop events
+    W.ctx.set_profiling(2)
+    for b in range(3):
+        W.ctx.sample_khop(W.batch(b)[1], spec.fanouts, 600 + b, out=bufs[0])
+        W.ctx.gather_features(bufs[0].gather_ids, n_dev=bufs[0].n_gather, out=outs[0])
+    torch.cuda.synchronize()
+    n = refs[2].gather_ids.size
+    assert outs[0][:n].cpu().numpy().tobytes() == rows_ref[2].tobytes()
+    prof = W.ctx.get_profile()
+    assert (prof.n_sample, prof.n_partition, prof.n_hit, prof.n_miss) == (0, 0, 3, 3)
+    assert 0 < prof.ms_hit < 50 and 0 < prof.ms_miss < 50 and prof.ms_sample == 0
+    W.ctx.set_profiling(0)
     W.ctx.check()
 
 
