@@ -294,7 +294,8 @@ int lgp_check(lgp_ctx* ctx, void* stream);
  * (hits, misses).  The gather launches record their own start and stop times; the groups
  * of several launches (sampling, partition) are bracketed by two recorded events, each of
  * which costs a few microseconds of stream time -- visible in steps that take a fraction of
- * a millisecond, hence mode 2.  lgp_get_profile waits for the recorded events, adds
+ * a millisecond, hence mode 2.  Keep profiling off while calls are captured into a HIP
+ * graph: timed launches are not capturable.  lgp_get_profile waits for the recorded events, adds
  * them up and resets. */
 int lgp_set_profiling(lgp_ctx* ctx, int mode);
 int lgp_get_profile(lgp_ctx* ctx, lgp_profile* out);
