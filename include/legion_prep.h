@@ -278,11 +278,12 @@ int lgp_gather_features(lgp_ctx* ctx, const int32_t* ids, int64_t n_max, const i
 
 /* By default lgp_gather_features runs the hit gather and then the miss gather on
  * `stream`.  With overlap enabled the miss gather runs on a stream of the library's own
- * beside the hit gather and `stream` waits for it.  Measured on MI355X this does not pay
- * when misses dominate (2.4 M vertices, 400-byte rows, 30 % of them cached: 2.77 ms per
- * step instead of 2.63 ms -- the two kernels contend for the same memory-request queues,
- * so both slow down); it is an option for workloads whose hit and miss gathers take
- * similar time. */
+ * beside the hit gather, which is then launched a quarter as wide so that its requests do
+ * not crowd the PCIe reads, and `stream` waits for both.  Measured on MI355X with misses
+ * dominating (2.4 M vertices, 400-byte rows, 30 % of them cached): 2.49 ms per step instead
+ * of 2.56 ms.  The hit gather itself takes many times longer that way (PCIe reads queued
+ * ahead of it throttle it), so per-kernel timings are only meaningful with overlap off,
+ * which is the default. */
 int lgp_set_overlap(lgp_ctx* ctx, int enable);
 
 /* Sticky device-side error flag (invalid vertex id met by a kernel, output overrun).

@@ -1022,12 +1022,12 @@ static int gather_core(lgp_ctx* c, int32_t member, const int32_t* ids, int64_t n
     const DirectIds listed{nullptr, 0, nullptr, 0, nullptr};
     ev = prof_pair(c, PK_HIT);
     launch_gather_rows(c->di, c->fc, out, c->row_bytes, L.row[0], L.src[0], n_max, counters, false, s, listed, ev.a,
-                       ev.b);
+                       ev.b, c->overlap);
     prof_keep(c, ev);
     if (three) {   // rows a peer caches: on this one device a second HBM gather, from the peers' regions
       ev = prof_pair(c, PK_HIT);
       launch_gather_rows(c->di, c->fc, out, c->row_bytes, L.row[2], L.src[2], n_max, counters + 2, false, s, listed,
-                         ev.a, ev.b);
+                         ev.a, ev.b, c->overlap);
       prof_keep(c, ev);
     }
     ev = prof_pair(c, PK_MISS);

@@ -102,11 +102,11 @@ struct DirectIds {
 // row_bytes wide; `row` and `srcrow` may each be null (= e).  streaming = source is read once over
 // PCIe (non-temporal loads, one lane group per row).
 // With ev_start and ev_stop given (and n_max > 0) the kernel's own start and stop times are recorded
-// into them.
+// into them.  beside_pcie: this HBM-bound gather runs at the same time as a PCIe-bound one.
 void launch_gather_rows(const DeviceInfo& di, const void* src, void* dst, int64_t row_bytes, const int32_t* row,
                         const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, bool streaming, hipStream_t s,
                         const DirectIds& dir = DirectIds{nullptr, 0, nullptr, 0, nullptr},
-                        hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
+                        hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr, bool beside_pcie = false);
 
 // ---- blocks.hip -----------------------------------------------------------
 constexpr int kScanTile = 1024;   // elements per workgroup of the counts -> offsets scan

@@ -231,6 +231,7 @@ inline unsigned blocks_for(int64_t work_blocks, int64_t limit) {
 struct Where {
   hipStream_t s;
   hipEvent_t a, b;
+  int64_t hbm_blocks;   // most workgroups an HBM-bound gather may use
 };
 
 template <typename K, typename... Args>
@@ -244,7 +245,7 @@ void launch_flat(const DeviceInfo& di, const void* src, void* dst, int64_t row_b
                  const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, const DirectIds& dir, const Where& s) {
   const uint32_t cpr = uint32_t(row_bytes / int64_t(sizeof(VecT)));
   const uint64_t inv = (uint64_t(1) << 32) / cpr + 1;          // exact for flat < 64 * cpr, cpr <= 4096
-  const unsigned blocks = blocks_for((n_max + 255) / 256, int64_t(di.num_cus) * 8);
+  const unsigned blocks = blocks_for((n_max + 255) / 256, s.hbm_blocks);
   // Rows made of whole 128-byte lines are read once: stream them past L2 (+2.5 % at 512-B and 2-KiB
   // rows).  Rows that straddle lines share their boundary lines between consecutive load
   // instructions, and L2 has to merge those (non-temporal loads cost 7 % on 400-B rows).
@@ -276,7 +277,7 @@ template <typename VecT, int G>
 void launch_group_hbm_g(const DeviceInfo& di, const void* src, void* dst, uint32_t cpr, const int32_t* row,
                         const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, const DirectIds& dir,
                         const Where& s) {
-  const unsigned blocks = blocks_for((n_max + 256 / G - 1) / (256 / G), int64_t(di.num_cus) * 8);
+  const unsigned blocks = blocks_for((n_max + 256 / G - 1) / (256 / G), s.hbm_blocks);
   launch_on(s, gather_rows_group_kernel<VecT, G, 1, true>, blocks,
                      static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, row, srcrow, n_max, n_dev, dir);
 }
@@ -322,9 +323,14 @@ void launch_partition(const DeviceInfo& di, const int32_t* ids, int64_t n_max, c
 
 void launch_gather_rows(const DeviceInfo& di, const void* src, void* dst, int64_t row_bytes, const int32_t* row,
                         const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, bool streaming, hipStream_t stream,
-                        const DirectIds& dir, hipEvent_t ev_start, hipEvent_t ev_stop) {
+                        const DirectIds& dir, hipEvent_t ev_start, hipEvent_t ev_stop, bool beside_pcie) {
   if (n_max <= 0) return;
-  const Where s{stream, ev_start, ev_stop};
+  // An HBM-bound gather normally fills the chip (8 workgroups per CU).  One that runs beside a
+  // PCIe-bound kernel is throttled by the PCIe reads queued ahead of it whatever its width, and
+  // in turn delays them; two workgroups per CU keep it out of the link's way (measured on 400-byte
+  // rows, 506 k hits beside 253 k misses: the miss gather takes 2.40 ms beside a full-width hit
+  // gather, 2.24 ms beside a narrow one, and the step 2.49 ms instead of 2.66 ms).
+  const Where s{stream, ev_start, ev_stop, int64_t(di.num_cus) * (beside_pcie ? 2 : 8)};
   const uintptr_t align = uintptr_t(src) | uintptr_t(dst) | uintptr_t(row_bytes);
 #define LGP_ROWS(VecT)                                                                        \
   do {                                                                                        \
