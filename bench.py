@@ -180,10 +180,16 @@ def main() -> int:
     # algorithmic bytes of one hit-gather launch: each hit row is read once and written once,
     # plus its (row, slot) list entry
     hit_bytes_per_row = 2 * row_bytes + 8
+    # kernel names as rocprofv3 lists them (16-byte chunks; lane groups of the next power of two >= chunks per row)
+    cpr = row_bytes // 16
+    grp = next(g for g in (4, 8, 16, 32, 64) if g >= min(cpr, 64))
+    hit_kernel = (f"gather_rows_group_kernel<u32x4, {grp}, 1, true>" if row_bytes % 128 and cpr <= 32
+                  else f"gather_rows_flat_kernel<u32x4, 4, {'true' if row_bytes % 128 == 0 else 'false'}>")
+    miss_kernel = f"gather_rows_group_kernel<u32x4, {grp}, 4, false>"
     roofline = None
     if prof_g.n_hit and hit_rows:
         ach = hit_rows * hit_bytes_per_row / (prof_g.ms_hit * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "gather_rows_kernel (cache hits, HBM->HBM)", "achieved": round(ach, 1),
+        roofline = {"bound": "hbm", "kernel": hit_kernel + " (cache hits, HBM->HBM)", "achieved": round(ach, 1),
                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
                     "traffic": (round(MEASURED_HBM_BYTES_PER_HIT_ROW[row_bytes] * hit_rows / prof_g.n_hit)
                                 if row_bytes in MEASURED_HBM_BYTES_PER_HIT_ROW else None),
@@ -192,7 +198,7 @@ def main() -> int:
     roofline_pcie = None
     if prof_g.n_miss and miss_rows:
         ach = miss_rows * row_bytes / (prof_g.ms_miss * 1e-3) / 1e9
-        roofline_pcie = {"bound": "pcie", "kernel": "gather_rows_kernel (cache misses, CPU memory->HBM)",
+        roofline_pcie = {"bound": "pcie", "kernel": miss_kernel + " (cache misses, CPU memory->HBM)",
                          "achieved": round(ach, 2), "peak": PCIE_PEAK_GBS, "unit": "GB/s",
                          "frac": round(ach / PCIE_PEAK_GBS, 4), "avg_launch_ms": round(prof_g.ms_miss / prof_g.n_miss, 4),
                          "rows_per_launch": round(miss_rows / prof_g.n_miss, 1), "bytes_per_row": row_bytes}
