@@ -38,6 +38,13 @@
 //     alpha).  N_T is a ratio of integers, so plans are compared exactly by cross
 //     multiplication instead of in floating point.
 //
+//   * clique of several GPUs (Algorithm 1 in full; Sec. 4.2.2 S2-S3; Sec. 3.1 O1): column sums,
+//     ranking, arg-max owner (ties, paper silent: lowest GPU index), per-GPU queues; each GPU
+//     caches the longest prefix of its own queue that fits its own budget; a GPU's extraction
+//     finds a row in its own cache, in a peer's, or in CPU memory.
+//   * batch generator and graph constructor (Sec. 5): a Philox-keyed shuffle of the tablet per
+//     epoch; per hop a bipartite block in CSR form over local numbering (format: paper silent).
+//
 // Every function has a pin in tests/ (known-answer vectors, brute force,
 // closed forms or library routines); none is "parity unpinned".
 
