@@ -4,9 +4,10 @@
 
 Shows the call sequence a training loop would use: pre-sampling, automatic split of one
 cache budget between topology and features, cache build, then per batch: epoch shuffle,
-k-hop sampling, graph construction and feature extraction, with sampling of the next
-batch running beside the extraction of the current one.  The feature matrix and the
-per-hop blocks of every batch are what a GNN layer stack would consume.
+k-hop sampling, graph construction and feature extraction on three streams -- the graph
+constructor beside the feature extractor of the same batch, the sampling of the next batch
+beside both -- with the miss gather overlapping the hit gather.  The feature matrix and
+the per-hop blocks of every batch are what a GNN layer stack would consume.
 """
 from __future__ import annotations
 
@@ -46,14 +47,16 @@ def main() -> None:
     print(f"cache plan: alpha = {best / 100:.2f} -> {plan.n_topo} topology rows ({plan.topo_bytes / 1e6:.0f} MB), "
           f"{plan.n_feat} feature rows ({plan.feat_bytes / 1e6:.0f} MB)")
 
+    ctx.set_overlap(0 < plan.n_feat < spec.num_vertices)        # both gathers have work: run them side by side
     n_batches = tablet.numel() // spec.batch
-    s_sample, s_gather = torch.cuda.Stream(), torch.cuda.Stream()
+    s_sample, s_gather, s_blocks = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
     bufs = [lgp.SampleBuffers(spec.num_vertices, spec.batch, spec.fanouts, last_frontier=True) for _ in range(2)]
     blks = [lgp.BlockBuffers(b) for b in bufs]
     rows = [torch.empty((bufs[0].gather_cap, spec.feat_dim), dtype=ctx.feat_torch_dtype, device="cuda") for _ in range(2)]
     stats = torch.zeros((n_batches, 2), dtype=torch.int32, device="cuda")
     sampled = [torch.cuda.Event() for _ in range(2)]
     consumed = [torch.cuda.Event() for _ in range(2)]
+    built = [torch.cuda.Event() for _ in range(2)]
     for epoch in range(args.epochs):
         order = lgp.shuffle_tablet(tablet, seed=spec.split_seed, epoch=epoch)       # batch generator
         torch.cuda.synchronize()
@@ -64,10 +67,13 @@ def main() -> None:
             if b >= 2:
                 s_sample.wait_event(consumed[k])
             ctx.sample_khop(seeds, spec.fanouts, spec.base_seed + epoch * n_batches + b, out=bufs[k], stream=s_sample)
-            ctx.build_blocks(seeds, spec.fanouts, bufs[k], out=blks[k], stream=s_sample)
             sampled[k].record(s_sample)
+            s_blocks.wait_event(sampled[k])
+            ctx.build_blocks(seeds, spec.fanouts, bufs[k], out=blks[k], stream=s_blocks)
+            built[k].record(s_blocks)
             s_gather.wait_event(sampled[k])
             ctx.gather_features(bufs[k].gather_ids, n_dev=bufs[k].n_gather, out=rows[k], stats=stats[b], stream=s_gather)
+            s_gather.wait_event(built[k])
             # ... a training step would consume rows[k] and blks[k] here, on s_gather ...
             consumed[k].record(s_gather)
         torch.cuda.synchronize()
