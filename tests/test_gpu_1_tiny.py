@@ -398,15 +398,18 @@ def test_overlap_profiling_and_three_stream_pipelining(W):
     W.ctx.check()
 
 
-def test_hip_graph_capture_and_replay(W):
+@pytest.mark.parametrize("overlap", [False, True])
+def test_hip_graph_capture_and_replay(W, overlap):
     """One batch's whole launch sequence (sampling, dedup, partition, both gathers) captured into a HIP graph and
     replayed with new seeds in the same buffer: every replay matches the oracle and the eager result.  The path
-    records no memset node; eager work and synchronisations run between replays."""
+    records no memset node; eager work and synchronisations run between replays.  With overlap on, the library's
+    own miss stream forks from and rejoins the captured stream."""
     from gpu_common import assert_batch_equal
     import paper_2305_16588_amd as lgp
     spec = W.spec
     W.ctx.build_hotness(W.tablet_dev, spec.batch, spec.fanouts, spec.base_seed)
     W.ctx.build_cache(*datagen.budgets(spec, W.E))
+    W.ctx.set_overlap(overlap)
     seeds_buf = W.tablet_dev[:spec.batch].clone()
     buf = lgp.SampleBuffers(W.V, spec.batch, spec.fanouts)
     rows = torch.empty((buf.gather_cap, spec.feat_dim), dtype=torch.float32, device="cuda")
@@ -434,6 +437,7 @@ def test_hip_graph_capture_and_replay(W):
         eager = lgp.SampleBuffers(W.V, spec.batch, spec.fanouts)
         W.ctx.sample_khop(seeds_dev, spec.fanouts, 31, out=eager)       # eager call between replays
         assert_batch_equal(ref, eager.to_host(seeds_dev), f"eager after replay {b}")
+    W.ctx.set_overlap(False)
     W.ctx.check()
 
 
