@@ -161,3 +161,18 @@ def test_clique_cache_mid_full_size():
         assert (HT[g] == rt).all() and (HF[g] == rf).all()
     tb, fb = datagen.budgets(spec, int(Wm.indices.size))
     check_clique(Wm, 4, HT, HF, tablets, tb // 4, fb // 4, n_batches=1)
+
+
+def test_clique_cache_large_full_size():
+    """The large workload (111 M vertices, int64 offsets, 512-byte rows) as a clique of two members with caches far
+    smaller than the graph: plans, cached ids, cached offsets, sampling, extracted bytes and the three counts
+    (contents beyond that are covered by what sampling and extraction return).  LGP_SMALL=1 runs it at 1/8 size."""
+    import os
+    from gpu_common import Workload
+    spec = datagen.LARGE
+    scale = 1.0 if os.environ.get("LGP_SMALL", "0") != "1" else 0.125
+    if scale != 1.0:
+        spec = datagen.scaled(spec, scale)
+    Wl = Workload(spec, device_gen="cuda")
+    HT, HF, tablets = member_hotness(Wl, 2, max_batches=4)
+    check_clique(Wl, 2, HT, HF, tablets, int(4e9 * scale), int(20e9 * scale), n_batches=1, contents=False)
