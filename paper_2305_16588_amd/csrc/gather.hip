@@ -2,7 +2,10 @@
 // cache lookup + hit/miss partition, then two row-gather launches -- hits move
 // HBM -> HBM, misses are read in place from CPU memory over PCIe.
 //
-// Row gather: a wavefront takes 64 list entries (one coalesced load of the row / source
+// Two row-gather kernels share the work.  The group kernel further down gives every row a
+// group of lanes: it serves the misses, the cache fill and the hits on rows that straddle
+// 128-byte lines.  The flat kernel serves hits on rows made of whole lines:
+// a wavefront takes 64 list entries (one coalesced load of the row / source
 // indices), then walks the 64 rows as one flat run of 16-byte chunks, so every lane
 // issues 128-bit loads and stores, a row of any 16-byte-multiple width keeps all lanes
 // busy, and several loads per lane are in flight before the first store.  The
