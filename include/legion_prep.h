@@ -286,6 +286,17 @@ int lgp_gather_features(lgp_ctx* ctx, const int32_t* ids, int64_t n_max, const i
  * which is the default. */
 int lgp_set_overlap(lgp_ctx* ctx, int enable);
 
+/* HBM the library holds or will allocate on its own for calls of one shape, in bytes, so that a
+ * caller can budget device memory before building caches (Sec. 4.3.1: B is what is left after
+ * everything else is reserved).  fixed [host] = the per-context tables that exist since
+ * lgp_create (row table, feature remap, hotness vectors, dedup bitmaps, rankings once a plan
+ * was made); scratch [host] = what pre-sampling, lgp_gather_features(_clique) with up to the
+ * worst-case number of ids and lgp_build_blocks allocate on first use for batches of up to
+ * max_seeds seeds with these fan-outs.  The caches themselves are reported by lgp_plan_cache /
+ * lgp_get_cache_plan.  Either pointer may be NULL.  Nothing is allocated or launched. */
+int lgp_workspace_bytes(const lgp_ctx* ctx, int32_t max_seeds, const int32_t* fanouts, int32_t n_hops, size_t* fixed,
+                        size_t* scratch);
+
 /* Sticky device-side error flag (invalid vertex id met by a kernel, output overrun).
  * Synchronises `stream`, returns LGP_EDEVICE if set, and clears it. */
 int lgp_check(lgp_ctx* ctx, void* stream);

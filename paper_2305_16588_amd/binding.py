@@ -61,7 +61,7 @@ class Profile(C.Structure):
 EXPORTS = ["lgp_host_alloc", "lgp_host_free", "lgp_shuffle_tablet", "lgp_create", "lgp_destroy", "lgp_build_hotness", "lgp_get_presample_stats", "lgp_get_hotness",
            "lgp_set_hotness", "lgp_plan_cache", "lgp_search_cache_plan", "lgp_cslp", "lgp_build_cache", "lgp_build_clique_cache", "lgp_get_clique_plan",
            "lgp_gather_features_clique", "lgp_get_cache_plan", "lgp_get_cache",
-           "lgp_sample_khop", "lgp_build_blocks", "lgp_gather_features", "lgp_set_overlap", "lgp_check", "lgp_set_profiling", "lgp_get_profile",
+           "lgp_sample_khop", "lgp_build_blocks", "lgp_gather_features", "lgp_set_overlap", "lgp_workspace_bytes", "lgp_check", "lgp_set_profiling", "lgp_get_profile",
            "lgp_strerror", "lgp_last_error"]
 
 _lib = None
@@ -99,6 +99,7 @@ def load_library():
     L.lgp_build_blocks.argtypes = [vp, vp, i32, vp, i32, C.POINTER(_SampleOut), C.POINTER(_BlocksOut), vp]
     L.lgp_gather_features.argtypes = [vp, vp, i64, vp, vp, vp, vp]
     L.lgp_set_overlap.argtypes = [vp, C.c_int]
+    L.lgp_workspace_bytes.argtypes = [vp, i32, vp, i32, vp, vp]
     L.lgp_check.argtypes = [vp, vp]
     L.lgp_set_profiling.argtypes = [vp, C.c_int]
     L.lgp_get_profile.argtypes = [vp, C.POINTER(Profile)]
@@ -427,6 +428,14 @@ class Context:
                                                     None if n_dev is None else n_dev.data_ptr(), out.data_ptr(),
                                                     None if stats is None else stats.data_ptr(), _stream_ptr(stream)))
         return out
+
+    def workspace_bytes(self, max_seeds: int, fanouts):
+        """(fixed, scratch) bytes of HBM the library holds / will allocate for batches of this shape (caches excluded)."""
+        fo = self._fanouts(fanouts)
+        fixed, scratch = C.c_size_t(), C.c_size_t()
+        self._ok(self._L.lgp_workspace_bytes(self._h, int(max_seeds), fo.ctypes.data, fo.size, C.byref(fixed),
+                                             C.byref(scratch)))
+        return fixed.value, scratch.value
 
     def check(self, stream=None):
         self._ok(self._L.lgp_check(self._h, _stream_ptr(stream)))

@@ -1058,6 +1058,33 @@ int lgp_gather_features_clique(lgp_ctx* c, int32_t member, const int32_t* ids, i
   return gather_core(c, member, ids, n_max, n_dev, out, stats, stream);
 }
 
+int lgp_workspace_bytes(const lgp_ctx* c, int32_t max_seeds, const int32_t* fanouts, int32_t n_hops, size_t* fixed,
+                        size_t* scratch) {
+  if (!c || max_seeds < 0) return LGP_EINVAL;
+  if (!fanouts || n_hops < 1) return LGP_EINVAL;
+  if (n_hops > LGP_MAX_HOPS) return LGP_EUNSUPPORTED;
+  for (int h = 0; h < n_hops; ++h) {
+    if (fanouts[h] < 1) return LGP_EINVAL;
+    if (fanouts[h] > LGP_MAX_FANOUT) return LGP_EUNSUPPORTED;
+  }
+  const size_t V = size_t(c->g.num_vertices);
+  if (fixed) {
+    const size_t bitmap = size_t(c->n_chunks) * size_t(kChunkWords) * 8;
+    // row table 8 + remap 4 + two hotness vectors 4 + 4 + two rankings 4 + 4 bytes per vertex
+    *fixed = V * 28 + 2 * bitmap + size_t(c->n_chunks) * 4 + 64;
+  }
+  if (scratch) {
+    int64_t need[LGP_MAX_HOPS + 1], gather_need;
+    worst_case(c, max_seeds, fanouts, n_hops, need, &gather_need);
+    size_t total = size_t(gather_need) * 6 * 4;                 // hit / miss / peer lists
+    total += size_t(n_hops + 1) * V * 4;                        // graph constructor: one position table per list
+    for (int h = 0; h < n_hops; ++h) total += (size_t(need[h]) / kScanTile + 1) * 8;
+    for (int h = 1; h < n_hops; ++h) total += size_t(need[h]) * 4;   // pre-sampling frontiers
+    *scratch = total;
+  }
+  return LGP_OK;
+}
+
 int lgp_check(lgp_ctx* c, void* stream) {
   if (!c) return LGP_EINVAL;
   LGP_HIP(c, hipSetDevice(c->di.device));

@@ -47,6 +47,7 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert lib.lgp_get_clique_plan(None, 0, None) == -1
     assert lib.lgp_gather_features_clique(None, 0, None, 0, None, None, None, None) == -1
     assert lib.lgp_build_blocks(None, None, 0, None, 0, None, None, None) == -1
+    assert lib.lgp_workspace_bytes(None, 1, None, 1, None, None) == -1
 
 
 def test_worst_case_sizes():

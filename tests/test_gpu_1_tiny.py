@@ -149,6 +149,21 @@ def test_determinism_same_call_twice(W):
     assert torch.equal(ra, rb)
 
 
+def test_workspace_bytes(W):
+    """The library's own HBM use for a batch shape, against the sizes of what it actually allocates."""
+    import paper_2305_16588_amd as lgp
+    fo = (10, 5)
+    fixed, scratch = W.ctx.workspace_bytes(1024, fo)
+    V = W.V
+    need, gather = lgp.worst_case_sizes(V, 1024, fo)
+    assert fixed >= 28 * V and fixed < 28 * V + 2 * (V * 32 // 8 + 8192 * 8) + 4096      # tables + two (sparse) bitmaps
+    want = 6 * 4 * gather + (len(fo) + 1) * V * 4 + sum((n // 1024 + 1) * 8 for n in need[:-1]) + 4 * sum(need[1:-1])
+    assert scratch == want
+    with pytest.raises(lgp.LegionPrepError) as e:
+        W.ctx.workspace_bytes(1024, (65,))
+    assert e.value.status == -4
+
+
 def test_argument_errors_are_reported_on_the_host(W):
     import paper_2305_16588_amd as lgp
     seeds_dev = W.tablet_dev[:100]
