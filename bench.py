@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 PCIE_PEAK_GBS = 63.0           # PCIe Gen5 x16, one direction: 32 GT/s * 16 * 128/130 / 8
 # HBM bytes per hit row measured with rocprofv3 --pmc (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors a plain
 # 1 GiB copy gives; see profiles/bench_{mid,large,share,wide}_workload.md), keyed by row width in bytes.
-MEASURED_HBM_BYTES_PER_HIT_ROW = {256: 516.3, 400: 931.5, 512: 1028.1, 2048: 4104.7}
+MEASURED_HBM_BYTES_PER_HIT_ROW = {256: 516.3, 400: 931.7, 512: 1028.1, 2048: 4105.0}
 
 
 def main() -> int:
