@@ -295,6 +295,91 @@ int plan_core(lgp_ctx* c, uint64_t topo_budget, uint64_t feat_budget, CachePlan*
   return st;
 }
 
+// member < 0: plain two-way extraction; member >= 0: three-way, as that member of the clique cache.
+int gather_core(lgp_ctx* c, int32_t member, const int32_t* ids, int64_t n_max, const int32_t* n_dev, void* out,
+                       int32_t* stats, void* stream) {
+  if (n_max < 0 || (n_max > 0 && (!ids || !out))) return fail(c, LGP_EINVAL, "ids / out / n_max");
+  if (!c->g.features) return fail(c, LGP_ESTATE, "the graph was created without a feature table");
+  if (n_max >= (int64_t(1) << 31)) return fail(c, LGP_EUNSUPPORTED, "more than 2^31 - 1 rows in one call");
+  const uintptr_t a = uintptr_t(out) | uintptr_t(c->row_bytes);
+  const int64_t vec = (a & 15u) == 0 ? 16 : (a & 7u) == 0 ? 8 : (a & 3u) == 0 ? 4 : (a & 1u) == 0 ? 2 : 0;
+  if (vec == 0 || c->row_bytes / vec > 4096) return fail(c, LGP_EUNSUPPORTED, "output alignment too small for this row width");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  LGP_HIP(c, hipSetDevice(c->di.device));
+  const bool three = member >= 0;
+  int32_t* counters = stats ? stats : c->counters;
+  PartLists L = {};
+  if (n_max == 0) {
+    launch_partition(c->di, ids, 0, nullptr, c->f_remap, c->g.num_vertices, L, three ? 3 : 2, 0, 0, counters, c->d_err,
+                     s);
+    return LGP_OK;
+  }
+  const int64_t V = c->g.num_vertices;
+  EvPair ev;
+  if (!three && c->plan.n_feat == V) {
+    // every row is cached: no partition, the id list is looked up by the gather itself
+    ev = prof_pair(c, PK_HIT);
+    launch_gather_rows(c->di, c->fc, out, c->row_bytes, nullptr, ids, n_max, n_dev, false, s,
+                       DirectIds{c->fc_identity ? nullptr : c->f_remap, V, counters, 0, c->d_err}, ev.a, ev.b);
+    prof_keep(c, ev);
+  } else if (!three && c->plan.n_feat == 0) {
+    // nothing is cached: every id is its own source row in CPU memory
+    ev = prof_pair(c, PK_MISS);
+    launch_gather_rows(c->di, c->g.features, out, c->row_bytes, nullptr, ids, n_max, n_dev, true, s,
+                       DirectIds{nullptr, V, counters, 1, c->d_err}, ev.a, ev.b);
+    prof_keep(c, ev);
+  } else {
+    if (n_max > c->list_cap) {                     // scratch for the lists grows on demand
+      LGP_HIP(c, hipStreamSynchronize(s));
+      LGP_HIP(c, hipStreamSynchronize(c->miss_stream));
+      if (c->lists) (void)hipFree(c->lists);
+      c->lists = nullptr;
+      c->list_cap = 0;
+      LGP_HIP(c, dev_alloc(&c->lists, size_t(n_max) * 6));
+      c->list_cap = n_max;
+    }
+    for (int l = 0; l < (three ? 3 : 2); ++l) {
+      L.row[l] = c->lists + (2 * l) * c->list_cap;
+      L.src[l] = c->lists + (2 * l + 1) * c->list_cap;
+    }
+    ev = prof_begin(c, PK_PARTITION, s);
+    launch_partition(c->di, ids, n_max, n_dev, c->f_remap, V, L, three ? 3 : 2,
+                     three ? int32_t(c->clique_fn[member]) : 0, three ? int32_t(c->clique_fn[member + 1]) : 0, counters,
+                     c->d_err, s);
+    prof_end(c, ev, s);
+    // Hits first (HBM -> HBM, short), then misses (PCIe, long).  With overlap enabled the
+    // misses run on a second stream beside the hits and rejoin `s` afterwards.
+    hipStream_t ms = s;
+    if (c->overlap) {
+      ms = c->miss_stream;
+      LGP_HIP(c, hipEventRecord(c->ev_fork, s));
+      LGP_HIP(c, hipStreamWaitEvent(ms, c->ev_fork, 0));
+    }
+    const DirectIds listed{nullptr, 0, nullptr, 0, nullptr};
+    ev = prof_pair(c, PK_HIT);
+    launch_gather_rows(c->di, c->fc, out, c->row_bytes, L.row[0], L.src[0], n_max, counters, false, s, listed, ev.a,
+                       ev.b, c->overlap);
+    prof_keep(c, ev);
+    if (three) {   // rows a peer caches: on this one device a second HBM gather, from the peers' regions
+      ev = prof_pair(c, PK_HIT);
+      launch_gather_rows(c->di, c->fc, out, c->row_bytes, L.row[2], L.src[2], n_max, counters + 2, false, s, listed,
+                         ev.a, ev.b, c->overlap);
+      prof_keep(c, ev);
+    }
+    ev = prof_pair(c, PK_MISS);
+    launch_gather_rows(c->di, c->g.features, out, c->row_bytes, L.row[1], L.src[1], n_max, counters + 1, true, ms,
+                       listed, ev.a, ev.b);
+    prof_keep(c, ev);
+    if (c->overlap) {
+      LGP_HIP(c, hipEventRecord(c->ev_join, ms));
+      LGP_HIP(c, hipStreamWaitEvent(s, c->ev_join, 0));
+    }
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail_hip(c, e, "gather kernel launch");
+  return LGP_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -956,91 +1041,6 @@ int lgp_build_blocks(lgp_ctx* c, const int32_t* seeds, int32_t n_seeds, const in
   launch_build_blocks(c->di, a, s);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail_hip(c, e, "graph constructor launch");
-  return LGP_OK;
-}
-
-// member < 0: plain two-way extraction; member >= 0: three-way, as that member of the clique cache.
-static int gather_core(lgp_ctx* c, int32_t member, const int32_t* ids, int64_t n_max, const int32_t* n_dev, void* out,
-                       int32_t* stats, void* stream) {
-  if (n_max < 0 || (n_max > 0 && (!ids || !out))) return fail(c, LGP_EINVAL, "ids / out / n_max");
-  if (!c->g.features) return fail(c, LGP_ESTATE, "the graph was created without a feature table");
-  if (n_max >= (int64_t(1) << 31)) return fail(c, LGP_EUNSUPPORTED, "more than 2^31 - 1 rows in one call");
-  const uintptr_t a = uintptr_t(out) | uintptr_t(c->row_bytes);
-  const int64_t vec = (a & 15u) == 0 ? 16 : (a & 7u) == 0 ? 8 : (a & 3u) == 0 ? 4 : (a & 1u) == 0 ? 2 : 0;
-  if (vec == 0 || c->row_bytes / vec > 4096) return fail(c, LGP_EUNSUPPORTED, "output alignment too small for this row width");
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  LGP_HIP(c, hipSetDevice(c->di.device));
-  const bool three = member >= 0;
-  int32_t* counters = stats ? stats : c->counters;
-  PartLists L = {};
-  if (n_max == 0) {
-    launch_partition(c->di, ids, 0, nullptr, c->f_remap, c->g.num_vertices, L, three ? 3 : 2, 0, 0, counters, c->d_err,
-                     s);
-    return LGP_OK;
-  }
-  const int64_t V = c->g.num_vertices;
-  EvPair ev;
-  if (!three && c->plan.n_feat == V) {
-    // every row is cached: no partition, the id list is looked up by the gather itself
-    ev = prof_pair(c, PK_HIT);
-    launch_gather_rows(c->di, c->fc, out, c->row_bytes, nullptr, ids, n_max, n_dev, false, s,
-                       DirectIds{c->fc_identity ? nullptr : c->f_remap, V, counters, 0, c->d_err}, ev.a, ev.b);
-    prof_keep(c, ev);
-  } else if (!three && c->plan.n_feat == 0) {
-    // nothing is cached: every id is its own source row in CPU memory
-    ev = prof_pair(c, PK_MISS);
-    launch_gather_rows(c->di, c->g.features, out, c->row_bytes, nullptr, ids, n_max, n_dev, true, s,
-                       DirectIds{nullptr, V, counters, 1, c->d_err}, ev.a, ev.b);
-    prof_keep(c, ev);
-  } else {
-    if (n_max > c->list_cap) {                     // scratch for the lists grows on demand
-      LGP_HIP(c, hipStreamSynchronize(s));
-      LGP_HIP(c, hipStreamSynchronize(c->miss_stream));
-      if (c->lists) (void)hipFree(c->lists);
-      c->lists = nullptr;
-      c->list_cap = 0;
-      LGP_HIP(c, dev_alloc(&c->lists, size_t(n_max) * 6));
-      c->list_cap = n_max;
-    }
-    for (int l = 0; l < (three ? 3 : 2); ++l) {
-      L.row[l] = c->lists + (2 * l) * c->list_cap;
-      L.src[l] = c->lists + (2 * l + 1) * c->list_cap;
-    }
-    ev = prof_begin(c, PK_PARTITION, s);
-    launch_partition(c->di, ids, n_max, n_dev, c->f_remap, V, L, three ? 3 : 2,
-                     three ? int32_t(c->clique_fn[member]) : 0, three ? int32_t(c->clique_fn[member + 1]) : 0, counters,
-                     c->d_err, s);
-    prof_end(c, ev, s);
-    // Hits first (HBM -> HBM, short), then misses (PCIe, long).  With overlap enabled the
-    // misses run on a second stream beside the hits and rejoin `s` afterwards.
-    hipStream_t ms = s;
-    if (c->overlap) {
-      ms = c->miss_stream;
-      LGP_HIP(c, hipEventRecord(c->ev_fork, s));
-      LGP_HIP(c, hipStreamWaitEvent(ms, c->ev_fork, 0));
-    }
-    const DirectIds listed{nullptr, 0, nullptr, 0, nullptr};
-    ev = prof_pair(c, PK_HIT);
-    launch_gather_rows(c->di, c->fc, out, c->row_bytes, L.row[0], L.src[0], n_max, counters, false, s, listed, ev.a,
-                       ev.b, c->overlap);
-    prof_keep(c, ev);
-    if (three) {   // rows a peer caches: on this one device a second HBM gather, from the peers' regions
-      ev = prof_pair(c, PK_HIT);
-      launch_gather_rows(c->di, c->fc, out, c->row_bytes, L.row[2], L.src[2], n_max, counters + 2, false, s, listed,
-                         ev.a, ev.b, c->overlap);
-      prof_keep(c, ev);
-    }
-    ev = prof_pair(c, PK_MISS);
-    launch_gather_rows(c->di, c->g.features, out, c->row_bytes, L.row[1], L.src[1], n_max, counters + 1, true, ms,
-                       listed, ev.a, ev.b);
-    prof_keep(c, ev);
-    if (c->overlap) {
-      LGP_HIP(c, hipEventRecord(c->ev_join, ms));
-      LGP_HIP(c, hipStreamWaitEvent(s, c->ev_join, 0));
-    }
-  }
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return fail_hip(c, e, "gather kernel launch");
   return LGP_OK;
 }
 
