@@ -389,13 +389,26 @@ def main() -> int:
         HT = torch.empty((K, V), dtype=torch.int32, device="cuda")
         HF = torch.empty((K, V), dtype=torch.int32, device="cuda")
         tabs = []
+        sum_t, sum_f, n_tsum_c = np.zeros(V, np.uint64), np.zeros(V, np.uint64), 0
         for g in range(K):
             tabs.append(tablet_dev[g::K].contiguous())
             ctx.build_hotness(tabs[g], spec.batch, spec.fanouts, spec.base_seed + 1000 * g)
             th, fh = ctx.get_hotness()
             HT[g].copy_(torch.from_numpy(th.view(np.int32)))
             HF[g].copy_(torch.from_numpy(fh.view(np.int32)))
-        plans = ctx.build_clique_cache(HT, HF, topo_b, feat_b)
+            sum_t += th
+            sum_f += fh
+            n_tsum_c += ctx.get_presample_stats()[1]
+        ctopo_b, cfeat_b, clique_plan = topo_b, feat_b, None
+        if args.cache_bytes:
+            # Sec. 4.3 at clique granularity: the cost model runs on the clique's summed hotness (A_T, A_F) with the
+            # clique's budget K * B and the clique's N_TSUM; every member then gets 1/K of each share.
+            ctx.build_cache(0, 0)                                   # drop the cache: the search re-ranks the vertices
+            ctx.set_hotness(np.minimum(sum_t, 2**32 - 1).astype(np.uint32), np.minimum(sum_f, 2**32 - 1).astype(np.uint32))
+            cbest, cpts = ctx.search_cache_plan(K * args.cache_bytes, n_tsum_c, cls_bytes=128)
+            ctopo_b, cfeat_b = int(cpts["m_topo"][cbest]) // K, int(cpts["m_feat"][cbest]) // K
+            clique_plan = {"B_per_member": args.cache_bytes, "alpha_by_cost_model": cbest / 100}
+        plans = ctx.build_clique_cache(HT, HF, ctopo_b, cfeat_b)
         del HT, HF
         my_batches = max(1, tabs[0].numel() // spec.batch)
         cstats = torch.zeros((args.steps + args.warmup, 3), dtype=torch.int32, device="cuda")
@@ -419,10 +432,13 @@ def main() -> int:
         tot = cstats[args.warmup:].sum(dim=0).tolist()
         clique = {"k_g": K, "member": 0, "value": round(args.steps * n_seeds / (c1 - c0), 1), "unit": "seeds/s",
                   "ms_per_step": round((c1 - c0) * 1e3 / args.steps, 4),
+                  "cache_plan": clique_plan,
                   "cached_topo_rows": [p.n_topo for p in plans], "cached_feat_rows": [p.n_feat for p in plans],
                   "rows_per_step": {"own_cache": round(tot[0] / args.steps, 1), "peer_cache": round(tot[2] / args.steps, 1),
                                     "cpu_memory": round(tot[1] / args.steps, 1)},
-                  "how": "hash split of the tablet; every member caches the workload's budgets; peers simulated in local HBM"}
+                  "how": "hash split of the tablet; every member caches "
+                         + ("1/K of the clique budget K * B, split by the cost model on the clique's summed hotness"
+                            if clique_plan else "the workload's budgets") + "; peers simulated in local HBM"}
         del tabs, cstats
 
     cpu = None
