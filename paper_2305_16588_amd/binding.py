@@ -68,12 +68,14 @@ _lib = None
 
 
 def load_library():
-    """Load liblegion_prep.so, building it first only if no built library exists."""
+    """Load liblegion_prep.so.  It is built first if no built library exists, or if the one that
+    exists was built from other sources than the ones in csrc/ and include/ now (a hash of the
+    sources is stored beside the library), so an edit never runs against an old binary."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_LIBPATH):
-        from . import build as _build
+    from . import build as _build
+    if not os.path.exists(_LIBPATH) or _build.is_stale():
         _build.build()
     L = C.CDLL(_LIBPATH)
     vp, i32, i64, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64

@@ -1,6 +1,7 @@
 """Compile liblegion_prep.so for gfx950 with hipcc (in-tree, no JIT cache)."""
 from __future__ import annotations
 
+import hashlib
 import os
 import subprocess
 import sys
@@ -10,6 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "liblegion_prep.so")
+STAMP = os.path.join(HERE, "liblegion_prep.srchash")   # hash of the sources the library was built from
 SOURCES = ["sampler.hip", "compact.hip", "gather.hip", "blocks.hip", "cache.hip", "api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
@@ -28,13 +30,40 @@ def _compile(src: str) -> str:
     return obj
 
 
+def source_hash() -> str:
+    """Hash of everything the library is compiled from (sources, headers, flags)."""
+    h = hashlib.sha256(" ".join(FLAGS[:-2]).encode())
+    files = [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC))]
+    files += [os.path.join(INCLUDE, f) for f in sorted(os.listdir(INCLUDE))]
+    for path in files:
+        if os.path.isfile(path):
+            h.update(os.path.basename(path).encode())
+            with open(path, "rb") as f:
+                h.update(f.read())
+    return h.hexdigest()
+
+
+def is_stale() -> bool:
+    """True if a built library exists but was not built from the sources as they are now."""
+    if not os.path.exists(LIB):
+        return False
+    try:
+        with open(STAMP) as f:
+            return f.read().strip() != source_hash()
+    except OSError:
+        return True
+
+
 def build(verbose: bool = False) -> str:
+    stamp = source_hash()
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
     r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], capture_output=True,
                        text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
+    with open(STAMP, "w") as f:
+        f.write(stamp + "\n")
     if verbose:
         print("built", LIB)
     return LIB

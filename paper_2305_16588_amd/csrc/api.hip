@@ -1120,15 +1120,22 @@ int lgp_get_profile(lgp_ctx* c, lgp_profile* out) {
   std::memset(out, 0, sizeof(*out));
   int64_t* counts[PK_COUNT] = {&out->n_sample, &out->n_partition, &out->n_hit, &out->n_miss};
   double* sums[PK_COUNT] = {&out->ms_sample, &out->ms_partition, &out->ms_hit, &out->ms_miss};
-  for (EvPair& p : c->ev_used) {
-    LGP_HIP(c, hipEventSynchronize(p.b));
+  // a pair leaves ev_used before it enters ev_free, so that an error in the middle of the loop
+  // leaves every pair in exactly one of the two lists (lgp_destroy destroys both)
+  hipError_t e = hipSuccess;
+  while (!c->ev_used.empty()) {
+    const EvPair p = c->ev_used.back();
+    c->ev_used.pop_back();
+    c->ev_free.push_back(p);
+    if (e != hipSuccess) continue;
     float ms = 0.f;
-    LGP_HIP(c, hipEventElapsedTime(&ms, p.a, p.b));
+    e = hipEventSynchronize(p.b);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, p.a, p.b);
+    if (e != hipSuccess) continue;
     *counts[p.kind] += 1;
     *sums[p.kind] += double(ms);
-    c->ev_free.push_back(p);
   }
-  c->ev_used.clear();
+  if (e != hipSuccess) return fail_hip(c, e, "reading the profiling events");
   return LGP_OK;
 }
 

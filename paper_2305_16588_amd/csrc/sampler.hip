@@ -5,8 +5,8 @@
 // whether its column ids sit in the HBM topology cache or in the CPU-resident CSR (read
 // in place over PCIe), so an uncached vertex costs one PCIe round trip, not two.  All slots draw their
 // Philox number at once; Floyd's sequential "already taken?" test becomes fanout-1
-// group broadcasts.  The kernel is bound by dependent-load latency, so it keeps the
-// register footprint small and the grid at full occupancy.
+// group broadcasts.  The kernel is bound by dependent loads and by the bitmap atomics, not by
+// issue slots, so the grid is capped at four workgroups per CU (see launch_one).
 #include "common.hpp"
 #include "philox_dev.hpp"
 
