@@ -276,6 +276,19 @@ int lgp_build_blocks(lgp_ctx* ctx, const int32_t* seeds, int32_t n_seeds, const 
 int lgp_gather_features(lgp_ctx* ctx, const int32_t* ids, int64_t n_max, const int32_t* n_dev, void* out,
                         int32_t* stats, void* stream);
 
+/* For callers that cannot allocate device memory -- code under HIP-graph capture without a warm-up call,
+ * tight serving loops, harnesses that forbid hipMalloc: lgp_gather_features with the same arguments, results
+ * and errors, but its scratch (the hit / miss counters and the four partition lists) lives in a fixed
+ * 64 MiB block of device memory that is part of the library image, so the call allocates and frees nothing,
+ * creates no events (it is never timed by lgp_set_profiling) and never synchronises.  n_max above
+ * LGP_STATIC_GATHER_MAX_IDS is refused with LGP_ECAPACITY before anything is launched.  Every call on a GPU,
+ * from any context, uses that GPU's one block: calls that overlap in time on one GPU race; order them on one
+ * stream or with events.  The block keeps the last call's contents; the call clears the counters itself with
+ * a small kernel (no memset node, so it may be captured) and never reads list entries it did not write. */
+#define LGP_STATIC_GATHER_MAX_IDS (1 << 22)
+int lgp_gather_features_static(lgp_ctx* ctx, const int32_t* ids, int64_t n_max, const int32_t* n_dev, void* out,
+                               int32_t* stats, void* stream);
+
 /* By default lgp_gather_features runs the hit gather and then the miss gather on
  * `stream`.  With overlap enabled the miss gather runs on a stream of the library's own
  * beside the hit gather, which is then launched a quarter as wide so that its requests do

@@ -17,6 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIBPATH = os.path.join(_HERE, "liblegion_prep.so")
 MAX_HOPS = 8
 MAX_FANOUT = 64
+STATIC_GATHER_MAX_IDS = 1 << 22
 
 
 class LegionPrepError(RuntimeError):
@@ -61,7 +62,7 @@ class Profile(C.Structure):
 EXPORTS = ["lgp_host_alloc", "lgp_host_free", "lgp_shuffle_tablet", "lgp_create", "lgp_destroy", "lgp_build_hotness", "lgp_get_presample_stats", "lgp_get_hotness",
            "lgp_set_hotness", "lgp_plan_cache", "lgp_search_cache_plan", "lgp_cslp", "lgp_build_cache", "lgp_build_clique_cache", "lgp_get_clique_plan",
            "lgp_gather_features_clique", "lgp_get_cache_plan", "lgp_get_cache",
-           "lgp_sample_khop", "lgp_build_blocks", "lgp_gather_features", "lgp_set_overlap", "lgp_workspace_bytes", "lgp_check", "lgp_set_profiling", "lgp_get_profile",
+           "lgp_sample_khop", "lgp_build_blocks", "lgp_gather_features", "lgp_gather_features_static", "lgp_set_overlap", "lgp_workspace_bytes", "lgp_check", "lgp_set_profiling", "lgp_get_profile",
            "lgp_strerror", "lgp_last_error"]
 
 _lib = None
@@ -100,6 +101,7 @@ def load_library():
     L.lgp_sample_khop.argtypes = [vp, vp, i32, vp, i32, u64, C.POINTER(_SampleOut), vp]
     L.lgp_build_blocks.argtypes = [vp, vp, i32, vp, i32, C.POINTER(_SampleOut), C.POINTER(_BlocksOut), vp]
     L.lgp_gather_features.argtypes = [vp, vp, i64, vp, vp, vp, vp]
+    L.lgp_gather_features_static.argtypes = [vp, vp, i64, vp, vp, vp, vp]
     L.lgp_set_overlap.argtypes = [vp, C.c_int]
     L.lgp_workspace_bytes.argtypes = [vp, i32, vp, i32, vp, vp]
     L.lgp_check.argtypes = [vp, vp]
@@ -414,6 +416,17 @@ class Context:
         self._ok(self._L.lgp_gather_features(self._h, ids.data_ptr(), n_max,
                                              None if n_dev is None else n_dev.data_ptr(), out.data_ptr(),
                                              None if stats is None else stats.data_ptr(), _stream_ptr(stream)))
+        return out
+
+    def gather_features_static(self, ids: torch.Tensor, n_dev: torch.Tensor | None, out: torch.Tensor,
+                               stats: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+        """gather_features through the library's fixed scratch block: allocates nothing, so `out` is required."""
+        assert ids.is_cuda and ids.dtype == torch.int32 and ids.is_contiguous()
+        n_max = ids.numel()
+        assert out.is_cuda and out.is_contiguous() and out.numel() * out.element_size() >= n_max * self.feat_dim * self.elem_bytes
+        self._ok(self._L.lgp_gather_features_static(self._h, ids.data_ptr(), n_max,
+                                                    None if n_dev is None else n_dev.data_ptr(), out.data_ptr(),
+                                                    None if stats is None else stats.data_ptr(), _stream_ptr(stream)))
         return out
 
     def gather_features_clique(self, member: int, ids: torch.Tensor, n_dev: torch.Tensor | None = None,

@@ -6,11 +6,37 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 using namespace lgp;
 
+// Scratch of lgp_gather_features_static: the hit / miss counters (first 64 words) and the four partition
+// lists (hit rows, hit slots, miss rows, miss ids; LGP_STATIC_GATHER_MAX_IDS entries each) -- 64 MiB that
+// every GPU this library runs on holds until the process ends.  In host code this name is only a handle
+// for hipGetSymbolAddress; kernels and copies use the per-device address kept in g_scratch.
+constexpr int64_t kStaticMaxIds = LGP_STATIC_GATHER_MAX_IDS;
+constexpr int64_t kStaticHeadWords = 64;
+static __device__ __align__(256) int32_t scratch[kStaticHeadWords + 4 * kStaticMaxIds];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+int32_t* g_scratch[kMaxDevices] = {};   // device address of `scratch` on each GPU, filled by lgp_create
+std::mutex g_scratch_mutex;
+
+// Look up, once per device and with that device current, where `scratch` lives on it.
+hipError_t resolve_scratch(int device) {
+  if (device < 0 || device >= kMaxDevices) return hipSuccess;   // the static entry point refuses such a device
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch[device]) return hipSuccess;
+  void* p = nullptr;
+  hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+  if (e != hipSuccess) return e;
+  if (!p) return hipErrorInvalidSymbol;
+  g_scratch[device] = static_cast<int32_t*>(p);
+  return hipSuccess;
+}
 
 enum ProfKind { PK_SAMPLE = 0, PK_PARTITION = 1, PK_HIT = 2, PK_MISS = 3, PK_COUNT = 4 };
 
@@ -296,8 +322,10 @@ int plan_core(lgp_ctx* c, uint64_t topo_budget, uint64_t feat_budget, CachePlan*
 }
 
 // member < 0: plain two-way extraction; member >= 0: three-way, as that member of the clique cache.
+// fixed != nullptr: the counters and lists live in that caller-provided block (kStaticHeadWords words, then
+// 2 * n_lists lists of fixed_cap entries); nothing is allocated, created or timed on this path.
 int gather_core(lgp_ctx* c, int32_t member, const int32_t* ids, int64_t n_max, const int32_t* n_dev, void* out,
-                       int32_t* stats, void* stream) {
+                       int32_t* stats, void* stream, int32_t* fixed = nullptr, int64_t fixed_cap = 0) {
   if (n_max < 0 || (n_max > 0 && (!ids || !out))) return fail(c, LGP_EINVAL, "ids / out / n_max");
   if (!c->g.features) return fail(c, LGP_ESTATE, "the graph was created without a feature table");
   if (n_max >= (int64_t(1) << 31)) return fail(c, LGP_EUNSUPPORTED, "more than 2^31 - 1 rows in one call");
@@ -307,7 +335,14 @@ int gather_core(lgp_ctx* c, int32_t member, const int32_t* ids, int64_t n_max, c
   hipStream_t s = static_cast<hipStream_t>(stream);
   LGP_HIP(c, hipSetDevice(c->di.device));
   const bool three = member >= 0;
-  int32_t* counters = stats ? stats : c->counters;
+  int32_t* counters = stats ? stats : fixed ? fixed : c->counters;
+  const int saved_profiling = c->profiling;
+  if (fixed) c->profiling = 0;                     // timing events are created on demand: not on this path
+  struct Restore {
+    lgp_ctx* c;
+    int mode;
+    ~Restore() { c->profiling = mode; }
+  } restore{c, saved_profiling};
   PartLists L = {};
   if (n_max == 0) {
     launch_partition(c->di, ids, 0, nullptr, c->f_remap, c->g.num_vertices, L, three ? 3 : 2, 0, 0, counters, c->d_err,
@@ -329,7 +364,9 @@ int gather_core(lgp_ctx* c, int32_t member, const int32_t* ids, int64_t n_max, c
                        DirectIds{nullptr, V, counters, 1, c->d_err}, ev.a, ev.b);
     prof_keep(c, ev);
   } else {
-    if (n_max > c->list_cap) {                     // scratch for the lists grows on demand
+    if (fixed) {
+      if (n_max > fixed_cap) return fail(c, LGP_ECAPACITY, "n_max exceeds LGP_STATIC_GATHER_MAX_IDS");
+    } else if (n_max > c->list_cap) {              // scratch for the lists grows on demand
       LGP_HIP(c, hipStreamSynchronize(s));
       LGP_HIP(c, hipStreamSynchronize(c->miss_stream));
       if (c->lists) (void)hipFree(c->lists);
@@ -338,9 +375,11 @@ int gather_core(lgp_ctx* c, int32_t member, const int32_t* ids, int64_t n_max, c
       LGP_HIP(c, dev_alloc(&c->lists, size_t(n_max) * 6));
       c->list_cap = n_max;
     }
+    int32_t* const lists = fixed ? fixed + kStaticHeadWords : c->lists;
+    const int64_t cap = fixed ? fixed_cap : c->list_cap;
     for (int l = 0; l < (three ? 3 : 2); ++l) {
-      L.row[l] = c->lists + (2 * l) * c->list_cap;
-      L.src[l] = c->lists + (2 * l + 1) * c->list_cap;
+      L.row[l] = lists + (2 * l) * cap;
+      L.src[l] = lists + (2 * l + 1) * cap;
     }
     ev = prof_begin(c, PK_PARTITION, s);
     launch_partition(c->di, ids, n_max, n_dev, c->f_remap, V, L, three ? 3 : 2,
@@ -442,6 +481,10 @@ int lgp_create(const lgp_graph* g, int device, lgp_ctx** out) {
     return status;
   };
   if (hipSetDevice(device) != hipSuccess) return bail(LGP_EHIP);
+  if (resolve_scratch(device) != hipSuccess) {
+    (void)hipGetLastError();
+    return bail(LGP_EHIP);
+  }
   c->di.device = device;
   hipDeviceProp_t prop;
   if (hipGetDeviceProperties(&prop, device) == hipSuccess) c->di.num_cus = prop.multiProcessorCount;
@@ -1048,6 +1091,15 @@ int lgp_gather_features(lgp_ctx* c, const int32_t* ids, int64_t n_max, const int
                         int32_t* stats, void* stream) {
   if (!c) return LGP_EINVAL;
   return gather_core(c, -1, ids, n_max, n_dev, out, stats, stream);
+}
+
+int lgp_gather_features_static(lgp_ctx* c, const int32_t* ids, int64_t n_max, const int32_t* n_dev, void* out,
+                               int32_t* stats, void* stream) {
+  if (!c) return LGP_EINVAL;
+  if (n_max > kStaticMaxIds) return fail(c, LGP_ECAPACITY, "n_max exceeds LGP_STATIC_GATHER_MAX_IDS");
+  int32_t* const block = (c->di.device >= 0 && c->di.device < kMaxDevices) ? g_scratch[c->di.device] : nullptr;
+  if (!block) return fail(c, LGP_EUNSUPPORTED, "no static scratch was set up for this device");
+  return gather_core(c, -1, ids, n_max, n_dev, out, stats, stream, block, kStaticMaxIds);
 }
 
 int lgp_gather_features_clique(lgp_ctx* c, int32_t member, const int32_t* ids, int64_t n_max, const int32_t* n_dev,
