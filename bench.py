@@ -86,7 +86,7 @@ class Inputs:
                                          dtype=torch.float32 if spec.feat_dtype == "float32" else torch.float16)
             for lo in range(0, spec.num_vertices, 1 << 22):
                 self.feats_src[lo:lo + (1 << 22)].copy_(torch.from_numpy(self.feats[lo:lo + (1 << 22)]))
-        self.tablet = datagen.make_tablet(spec)
+        self.tablet = datagen.make_tablet(spec, device="cuda")
         self.t_gen = time.time() - t0
         self.V, self.E, self.D = spec.num_vertices, int(self.indices.size), spec.feat_dim
         self.row_bytes = self.D * self.feats.dtype.itemsize

@@ -15,8 +15,15 @@ Graph recipe (directed Chung-Lu, power-law expected degrees):
     permutations (one for sources, one for targets), so hubs are scattered;
   * self-loops and duplicate (src, dst) pairs are dropped and every row is
     sorted, giving a simple graph in CSR form.
-All draws come from a torch.Generator seeded by the caller; for a given seed,
-torch build and device the result is reproducible.
+Every random value is a pure function of (seed, stream, index): a Philox4x32-10
+generator written here with exact integer tensor operations (it is this module's
+own; neither the oracle nor the library shares it), so a graph, a feature table
+or a tablet is the same whether it is generated on the CPU or on a GPU, in one
+piece or in chunks.  The two smooth functions of the recipe (expected degree by
+rank, inverse CDF of the target law) and the normal quantile function are
+tabulated once on the host and interpolated linearly with separate, exactly
+rounded multiply / add operations, so no device-dependent libm result ever
+decides an integer.
 """
 from __future__ import annotations
 
@@ -71,6 +78,79 @@ def scaled(spec: WorkloadSpec, factor: float, name: str | None = None) -> Worklo
                    num_edges=max(1, int(spec.num_edges * factor)))
 
 
+# ---- counter-based random numbers ------------------------------------------
+_M0, _M1, _W0, _W1, _MASK = 0xD2511F53, 0xCD9E8D57, 0x9E3779B9, 0xBB67AE85, 0xFFFFFFFF
+# streams (third counter word): one per kind of draw, so no two draws share a counter
+_S_DEG, _S_DEAD, _S_PERM_SRC, _S_PERM_DST, _S_EDGE, _S_FEAT, _S_SPLIT = range(7)
+
+
+def philox_rounds(c0, c1, c2, c3, k0: int, k1: int):
+    """Philox4x32-10 (Salmon et al., SC'11): counter words as int64 tensors holding 32-bit values, key words
+    as Python ints.  Returns the four output words as int64 tensors in [0, 2^32)."""
+    k0, k1 = k0 & _MASK, k1 & _MASK
+    for _ in range(10):
+        # 32 x 32 -> 64-bit products: the operands are below 2^32, so the wrapped int64 product holds
+        # the exact low 64 bits; an arithmetic shift followed by the mask recovers the high word
+        p0 = c0 * _M0
+        p1 = c2 * _M1
+        hi0, lo0 = (p0 >> 32) & _MASK, p0 & _MASK
+        hi1, lo1 = (p1 >> 32) & _MASK, p1 & _MASK
+        c0 = hi1 ^ c1 ^ k0
+        c2 = hi0 ^ c3 ^ k1
+        c1, c3 = lo1, lo0
+        k0, k1 = (k0 + _W0) & _MASK, (k1 + _W1) & _MASK
+    return c0, c1, c2, c3
+
+
+def philox4x32_10(idx: torch.Tensor, stream: int, seed: int):
+    """One generator call per entry of idx: counter = (idx low word, idx high word, stream, 0),
+    key = (seed low word, seed high word)."""
+    return philox_rounds(idx & _MASK, (idx >> 32) & _MASK, torch.full_like(idx, stream & _MASK),
+                         torch.zeros_like(idx), seed, seed >> 32)
+
+
+def _uniform_pair(idx: torch.Tensor, stream: int, seed: int):
+    """Two float64 uniforms in [0, 1) per index, each from 53 random bits (exact)."""
+    w0, w1, w2, w3 = philox4x32_10(idx, stream, seed)
+    a = ((w0 << 21) | (w1 >> 11)).to(torch.float64) * (2.0 ** -53)
+    b = ((w2 << 21) | (w3 >> 11)).to(torch.float64) * (2.0 ** -53)
+    return a, b
+
+
+def _uniform(first: int, n: int, stream: int, seed: int, dev) -> torch.Tensor:
+    """Uniforms number first .. first + n - 1 of a stream (two per generator call)."""
+    lo, hi = first // 2, (first + n + 1) // 2
+    a, b = _uniform_pair(torch.arange(lo, hi, device=dev, dtype=torch.int64), stream, seed)
+    u = torch.stack((a, b), dim=1).reshape(-1)
+    return u[first - 2 * lo:first - 2 * lo + n]
+
+
+def _permutation(n: int, stream: int, seed: int, dev) -> torch.Tensor:
+    """Permutation of 0 .. n-1: positions ordered by a 63-bit random key (ties by position)."""
+    w0, w1, _, _ = philox4x32_10(torch.arange(n, device=dev, dtype=torch.int64), stream, seed)
+    key = (w0 << 31) | (w1 >> 1)
+    return torch.sort(key, stable=True).indices
+
+
+class _Table:
+    """A smooth function tabulated at knots + 1 evenly spaced points of [0, span) on the host and
+    interpolated linearly on any device with separately rounded operations."""
+
+    def __init__(self, fn, span: float, knots: int, dev, dtype=torch.float64):
+        x = np.arange(knots + 1, dtype=np.float64) * (span / knots)
+        self.values = torch.from_numpy(np.asarray(fn(x), dtype=np.float64)).to(dtype).to(dev)
+        self.scale = knots / span
+        self.knots = knots
+
+    def __call__(self, x: torch.Tensor) -> torch.Tensor:
+        pos = x * self.scale
+        k = pos.floor().clamp_(0, self.knots - 1)
+        t = pos - k
+        k = k.to(torch.int64)
+        lo, hi = self.values[k], self.values[k + 1]
+        return lo + (hi - lo) * t
+
+
 def _series_sum(V: int, i0: float, beta: float) -> float:
     """sum_{i=0}^{V-1} (i + i0)^(-beta) by Euler-Maclaurin (i0 >> 1)."""
     a, b = i0, i0 + V - 1.0
@@ -109,37 +189,36 @@ def make_graph(spec: WorkloadSpec, device: str = "cpu", isolated: float = 0.001,
     """
     V, E = spec.num_vertices, spec.num_edges
     dev = torch.device(device)
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(spec.gen_seed)
+    seed = spec.gen_seed
     c, i0, beta = _solve_law(V, E, spec.gamma)
+    knots = 1 << 20
 
     # expected degree by rank -> integer degree by rank
+    weight = _Table(lambda r: c * (r + i0) ** (-beta), float(V), knots, dev)
     deg_rank = torch.empty(V, dtype=torch.int64, device=dev)
     step = 1 << 24
     for lo in range(0, V, step):
         hi = min(V, lo + step)
-        r = torch.arange(lo, hi, device=dev, dtype=torch.float64)
-        w = c * (r + i0) ** (-beta)
+        w = weight(torch.arange(lo, hi, device=dev, dtype=torch.float64))
         fl = torch.floor(w)
-        u = torch.rand(hi - lo, generator=gen, device=dev, dtype=torch.float64)
-        d = fl + (u < (w - fl)).to(torch.float64)
-        dead = torch.rand(hi - lo, generator=gen, device=dev) < isolated
-        d[dead] = 0
+        d = fl + (_uniform(lo, hi - lo, _S_DEG, seed, dev) < (w - fl)).to(torch.float64)
+        d[_uniform(lo, hi - lo, _S_DEAD, seed, dev) < isolated] = 0
         deg_rank[lo:hi] = d.to(torch.int64)
-    perm_src = torch.randperm(V, generator=gen, device=dev)   # rank -> source vertex id
-    perm_dst = torch.randperm(V, generator=gen, device=dev)   # rank -> target vertex id
+    perm_src = _permutation(V, _S_PERM_SRC, seed, dev)        # rank -> source vertex id
+    perm_dst = _permutation(V, _S_PERM_DST, seed, dev)        # rank -> target vertex id
     deg = torch.empty(V, dtype=torch.int64, device=dev)
     deg[perm_src] = deg_rank                                  # requested out-degree per vertex id
     del deg_rank, perm_src
 
     a, b = i0, i0 + float(V)
     if abs(beta - 1.0) < 1e-12:
-        def inv_cdf(u):
+        def inv_cdf_host(u):
             return a * (b / a) ** u - a
     else:
         pa, pb = a ** (1 - beta), b ** (1 - beta)
-        def inv_cdf(u):
+        def inv_cdf_host(u):
             return (pa + u * (pb - pa)) ** (1.0 / (1 - beta)) - a
+    inv_cdf = _Table(inv_cdf_host, 1.0, knots, dev)
 
     # rows are produced in chunks of consecutive vertex ids holding <= chunk_edges draws
     csum = torch.cumsum(deg, 0)
@@ -154,13 +233,15 @@ def make_graph(spec: WorkloadSpec, device: str = "cpu", isolated: float = 0.001,
     indices_full = indices_alloc(total_draws) if indices_alloc is not None else np.empty(total_draws, dtype=np.int32)
     dst_t = torch.from_numpy(indices_full) if total_draws else None
     at = 0
+    drawn = 0
     for lo, hi in zip(bounds[:-1], bounds[1:]):
         d = deg[lo:hi]
         n = int(d.sum().item())
         if n == 0:
             continue
         src = torch.repeat_interleave(torch.arange(lo, hi, device=dev, dtype=torch.int64), d)
-        u = torch.rand(n, generator=gen, device=dev, dtype=torch.float64)
+        u = _uniform(drawn, n, _S_EDGE, seed, dev)              # draw number = position in the requested edge list
+        drawn += n
         rank = inv_cdf(u).floor().to(torch.int64).clamp_(0, V - 1)
         del u
         dst = perm_dst[rank]
@@ -190,30 +271,39 @@ def make_graph(spec: WorkloadSpec, device: str = "cpu", isolated: float = 0.001,
 
 
 def make_features(spec: WorkloadSpec, device: str = "cpu", out: np.ndarray | None = None, chunk_rows: int = 1 << 20):
-    """[V, D] table of N(0,1) draws (fp32, or fp32 rounded to fp16)."""
+    """[V, D] table of N(0,1) draws (fp32, or fp32 rounded to fp16).  Element number e = v * D + c uses word
+    e mod 4 of generator call e div 4; the normal quantile function is tabulated on the host at 2^16 + 1
+    points and interpolated in fp32."""
     V, D = spec.num_vertices, spec.feat_dim
     npdt = np.float32 if spec.feat_dtype == "float32" else np.float16
     tdt = torch.float32 if spec.feat_dtype == "float32" else torch.float16
     dev = torch.device(device)
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(spec.feat_seed)
     if out is None:
         out = np.empty((V, D), dtype=npdt)
+
+    def quantile(p):
+        p = np.clip(p, 2.0 ** -33, 1.0 - 2.0 ** -33)
+        return (torch.erfinv(torch.from_numpy(2.0 * p - 1.0)) * math.sqrt(2.0)).numpy()
+
+    table = _Table(quantile, 1.0, 1 << 16, dev, dtype=torch.float32)
     for lo in range(0, V, chunk_rows):
         hi = min(V, lo + chunk_rows)
-        x = torch.randn(hi - lo, D, generator=gen, device=dev, dtype=torch.float32).to(tdt)
+        first, n = lo * D, (hi - lo) * D
+        c_lo, c_hi = first // 4, (first + n + 3) // 4
+        words = torch.stack(philox4x32_10(torch.arange(c_lo, c_hi, device=dev, dtype=torch.int64), _S_FEAT,
+                                          spec.feat_seed), dim=1).reshape(-1)[first - 4 * c_lo:first - 4 * c_lo + n]
+        u = (words.to(torch.float32) + 0.5) * (2.0 ** -32)      # fp32 rounding of the word: the same on every device
+        x = table(u.clamp_(0.0, 1.0 - 2.0 ** -24)).reshape(hi - lo, D).to(tdt)
         torch.from_numpy(out[lo:hi]).copy_(x)
     return out
 
 
-def make_tablet(spec: WorkloadSpec) -> np.ndarray:
+def make_tablet(spec: WorkloadSpec, device: str = "cpu") -> np.ndarray:
     """Training tablet: the first train_frac * V entries of a seeded permutation,
     already in epoch order (consecutive slices of `batch` are the mini-batches)."""
-    gen = torch.Generator()
-    gen.manual_seed(spec.split_seed)
-    perm = torch.randperm(spec.num_vertices, generator=gen)
+    perm = _permutation(spec.num_vertices, _S_SPLIT, spec.split_seed, torch.device(device))
     n = max(1, int(round(spec.train_frac * spec.num_vertices)))
-    return perm[:n].to(torch.int32).numpy().copy()
+    return perm[:n].to(torch.int32).cpu().numpy().copy()
 
 
 def budgets(spec: WorkloadSpec, num_edges: int):

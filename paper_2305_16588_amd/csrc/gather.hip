@@ -130,18 +130,22 @@ __global__ __launch_bounds__(256) void gather_rows_flat_kernel(const VecT* __res
                                                                uint32_t cpr, uint64_t inv_cpr,
                                                                const int32_t* __restrict__ row,
                                                                const int32_t* __restrict__ srcrow, int64_t n_max,
-                                                               const int32_t* __restrict__ n_dev, DirectIds dir) {
+                                                               const int32_t* __restrict__ n_dev, DirectIds dir,
+                                                               int epw) {
   int64_t n = n_dev ? int64_t(*n_dev) : n_max;
   if (n > n_max) n = n_max;
   direct_stats(dir, n);
   const int lane = threadIdx.x & 63;
   const int64_t wave = (int64_t(blockIdx.x) * 256 + threadIdx.x) >> 6;
   const int64_t n_waves = int64_t(gridDim.x) * 4;
-  for (int64_t e0 = wave * 64; e0 < n; e0 += n_waves * 64) {
+  // epw (<= 64) list entries per wave and pass: fewer for wide rows, so that a pass moves a few tens of
+  // KiB and the passes spread evenly over the waves whatever the (device-side) number of entries is
+  for (int64_t e0 = wave * epw; e0 < n; e0 += n_waves * epw) {
     const int64_t e = e0 + lane;
-    const int32_t my_row = e < n ? (row ? row[e] : int32_t(e)) : 0;
-    const int32_t my_src = direct_source(dir, e < n ? (srcrow ? srcrow[e] : int32_t(e)) : 0, e < n);
-    const uint32_t entries = uint32_t(n - e0 < 64 ? n - e0 : 64);
+    const bool mine = lane < epw && e < n;
+    const int32_t my_row = mine ? (row ? row[e] : int32_t(e)) : 0;
+    const int32_t my_src = direct_source(dir, mine ? (srcrow ? srcrow[e] : int32_t(e)) : 0, mine);
+    const uint32_t entries = uint32_t(n - e0 < epw ? n - e0 : epw);
     const uint32_t total = entries * cpr;          // chunks in this wave's 64 rows
     for (uint32_t f0 = 0; f0 < total; f0 += 64 * UNROLL) {
       VecT val[UNROLL];
@@ -248,16 +252,26 @@ void launch_flat(const DeviceInfo& di, const void* src, void* dst, int64_t row_b
                  const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, const DirectIds& dir, const Where& s) {
   const uint32_t cpr = uint32_t(row_bytes / int64_t(sizeof(VecT)));
   const uint64_t inv = (uint64_t(1) << 32) / cpr + 1;          // exact for flat < 64 * cpr, cpr <= 4096
-  const unsigned blocks = blocks_for((n_max + 255) / 256, s.hbm_blocks);
+  // Three workgroups (12 waves) per CU: the flat walk keeps 4 x 16 bytes per lane in flight, and more
+  // waves than that only add concurrent streams for the memory system to interleave -- measured hit
+  // gather at 8 / 4 / 3 / 2 workgroups per CU: 51.3 / 48.9 / 48.3 / 49.0 us on 505 k 256-byte rows,
+  // 163.1 / 157.4 / 155.3 / 156.5 us on 855 k 512-byte rows, 335.7 / 315.3 / 310.4 / 307.2 us on 379 k
+  // 2-KiB rows.  A narrower gather also leaves room for a sampler running beside it on another stream.
+  // A wave takes at most 32 KiB of rows per pass (64 rows of up to 512 bytes, 16 rows of 2 KiB): the number
+  // of entries is only known on the device, and with 128 KiB passes a launch of 233 k 2-KiB rows left most
+  // waves with one pass and a few with two (216.6 -> 195.7 us; 379 k such rows: 311.5 -> 263.8 us).
+  int epw = 64;
+  while (epw > 4 && int64_t(epw) * row_bytes > 32768) epw >>= 1;
+  const unsigned blocks = blocks_for((n_max + 4 * epw - 1) / (4 * epw), std::min<int64_t>(s.hbm_blocks, int64_t(di.num_cus) * 3));
   // Rows made of whole 128-byte lines are read once: stream them past L2 (+2.5 % at 512-B and 2-KiB
   // rows).  Rows that straddle lines share their boundary lines between consecutive load
   // instructions, and L2 has to merge those (non-temporal loads cost 7 % on 400-B rows).
   if (row_bytes % 128 == 0)
     launch_on(s, gather_rows_flat_kernel<VecT, 4, true>, blocks,
-                       static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, inv, row, srcrow, n_max, n_dev, dir);
+                       static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, inv, row, srcrow, n_max, n_dev, dir, epw);
   else
     launch_on(s, gather_rows_flat_kernel<VecT, 4, false>, blocks,
-                       static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, inv, row, srcrow, n_max, n_dev, dir);
+                       static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, inv, row, srcrow, n_max, n_dev, dir, epw);
 }
 
 template <typename VecT, int G>
@@ -280,7 +294,9 @@ template <typename VecT, int G>
 void launch_group_hbm_g(const DeviceInfo& di, const void* src, void* dst, uint32_t cpr, const int32_t* row,
                         const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, const DirectIds& dir,
                         const Where& s) {
-  const unsigned blocks = blocks_for((n_max + 256 / G - 1) / (256 / G), s.hbm_blocks);
+  // one row per group in flight needs more waves than the flat walk: 6 workgroups per CU (400-byte rows,
+  // 512 k hits: 138.7 / 107.6 / 95.6 / 90.7 / 91.4 us at 2 / 3 / 4 / 6 / 8 workgroups per CU)
+  const unsigned blocks = blocks_for((n_max + 256 / G - 1) / (256 / G), std::min<int64_t>(s.hbm_blocks, int64_t(di.num_cus) * 6));
   launch_on(s, gather_rows_group_kernel<VecT, G, 1, true>, blocks,
                      static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, row, srcrow, n_max, n_dev, dir);
 }
@@ -328,7 +344,7 @@ void launch_gather_rows(const DeviceInfo& di, const void* src, void* dst, int64_
                         const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, bool streaming, hipStream_t stream,
                         const DirectIds& dir, hipEvent_t ev_start, hipEvent_t ev_stop, bool beside_pcie) {
   if (n_max <= 0) return;
-  // An HBM-bound gather normally fills the chip (8 workgroups per CU).  One that runs beside a
+  // An HBM-bound gather is capped at 8 workgroups per CU (each kernel narrows that further).  One that runs beside a
   // PCIe-bound kernel is throttled by the PCIe reads queued ahead of it whatever its width, and
   // in turn delays them; two workgroups per CU keep it out of the link's way (measured on 400-byte
   // rows, 506 k hits beside 253 k misses: the miss gather takes 2.40 ms beside a full-width hit

@@ -35,7 +35,7 @@ def main() -> None:
     feats = lgp.pinned_empty((spec.num_vertices, spec.feat_dim),
                              np.float32 if spec.feat_dtype == "float32" else np.float16)
     datagen.make_features(spec, device="cuda", out=feats)
-    tablet = torch.from_numpy(datagen.make_tablet(spec)).cuda()
+    tablet = torch.from_numpy(datagen.make_tablet(spec, device="cuda")).cuda()
     ctx = lgp.Context(indptr, indices, feats)
 
     # cache construction: pre-sampling -> cost model picks alpha -> fill

@@ -27,7 +27,7 @@ class Workload:
             else:
                 self.features = lgp.pinned_empty((spec.num_vertices, spec.feat_dim), npdt)
             datagen.make_features(spec, device=device_gen, out=self.features)
-        self.tablet = datagen.make_tablet(spec)
+        self.tablet = datagen.make_tablet(spec, device=device_gen)
         self.tablet_dev = torch.from_numpy(self.tablet).cuda()
         self.features_dev = None
         if with_features and features_on_device:
