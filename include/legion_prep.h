@@ -240,6 +240,12 @@ int lgp_gather_features_clique(lgp_ctx* ctx, int32_t member, const int32_t* ids,
 int lgp_get_cache(lgp_ctx* ctx, int32_t* topo_ids, int64_t* t_indptr, int32_t* t_indices, int32_t* feat_ids,
                   void* feat_rows);
 
+/* A slice of the cache contents, for inspecting caches too large to copy in one piece.  which = 0:
+ * t_indices[first .. first + count), int32 entries; which = 1: the feature rows of ranks first ..
+ * first + count - 1, row_bytes each (rank order, as lgp_get_cache returns them).  dst is [host].
+ * LGP_EINVAL if the range leaves the cache.  Synchronous. */
+int lgp_get_cache_part(lgp_ctx* ctx, int32_t which, int64_t first, int64_t count, void* dst);
+
 /* k-hop uniform neighbour sampling of one mini-batch (Sec. 2.2 step 2; the neighbour
  * sampler of Sec. 5).  seeds is [device], n_seeds distinct ids; fanouts is [host],
  * 1 <= fanouts[h] <= LGP_MAX_FANOUT, 1 <= n_hops <= LGP_MAX_HOPS.  A vertex of degree
@@ -257,9 +263,9 @@ int lgp_sample_khop(lgp_ctx* ctx, const int32_t* seeds, int32_t n_seeds, const i
  * and `sampled`, with sampled->frontier[n_hops] given) and writes, per hop h, a bipartite
  * block in CSR form whose destinations are frontier h and whose sources are frontier h+1,
  * plus for every frontier the rows of its vertices in the extracted feature matrix.
- * Everything is read from device memory; no host synchronisation.  The first call (and a
- * later one with more hops) allocates n_hops + 1 lookup tables of V 4-byte entries and a
- * small scan scratch, and synchronises once. */
+ * Everything is read from device memory; no host synchronisation.  Unless lgp_reserve sized
+ * the scratch beforehand, the first call (and a later one with more hops) allocates n_hops + 1
+ * lookup tables of V 4-byte entries and a small scan scratch, and synchronises once. */
 int lgp_build_blocks(lgp_ctx* ctx, const int32_t* seeds, int32_t n_seeds, const int32_t* fanouts, int32_t n_hops,
                      const lgp_sample_out* sampled, const lgp_blocks_out* out, void* stream);
 
@@ -271,8 +277,8 @@ int lgp_build_blocks(lgp_ctx* ctx, const int32_t* seeds, int32_t n_seeds, const 
  * PCIe); stats [device int32[2], may be NULL] receives {n_hit, n_miss} (unspecified if
  * lgp_check then reports an invalid id).  When every row is cached, or none, the split is
  * skipped and one gather looks the ids up itself.  Otherwise scratch for the two lists
- * grows on demand (a growth step allocates and synchronises), so call once with the
- * largest n_max before capturing the call into a HIP graph. */
+ * grows on demand (a growth step allocates and synchronises) unless lgp_reserve sized it
+ * beforehand; lgp_gather_features_static needs neither. */
 int lgp_gather_features(lgp_ctx* ctx, const int32_t* ids, int64_t n_max, const int32_t* n_dev, void* out,
                         int32_t* stats, void* stream);
 
@@ -309,6 +315,15 @@ int lgp_set_overlap(lgp_ctx* ctx, int enable);
  * lgp_get_cache_plan.  Either pointer may be NULL.  Nothing is allocated or launched. */
 int lgp_workspace_bytes(const lgp_ctx* ctx, int32_t max_seeds, const int32_t* fanouts, int32_t n_hops, size_t* fixed,
                         size_t* scratch);
+
+/* Allocate, now, every scratch buffer that lgp_sample_khop, lgp_build_blocks, lgp_gather_features(_clique)
+ * and lgp_build_hotness use for batches of up to max_seeds seeds with these fan-outs (the amount
+ * lgp_workspace_bytes reports as `scratch`).  Afterwards those per-batch calls never allocate, free or
+ * synchronise -- they may be captured into a HIP graph without a warm-up call -- and a call whose shape
+ * exceeds the reservation returns LGP_ECAPACITY instead of growing the scratch.  May be called again with a
+ * larger shape.  Without it the scratch grows on demand, as described at each call.  fanouts is [host].
+ * Synchronous. */
+int lgp_reserve(lgp_ctx* ctx, int32_t max_seeds, const int32_t* fanouts, int32_t n_hops);
 
 /* Sticky device-side error flag (invalid vertex id met by a kernel, output overrun).
  * Synchronises `stream`, returns LGP_EDEVICE if set, and clears it. */

@@ -61,7 +61,7 @@ class Profile(C.Structure):
 
 EXPORTS = ["lgp_host_alloc", "lgp_host_free", "lgp_shuffle_tablet", "lgp_create", "lgp_destroy", "lgp_build_hotness", "lgp_get_presample_stats", "lgp_get_hotness",
            "lgp_set_hotness", "lgp_plan_cache", "lgp_search_cache_plan", "lgp_cslp", "lgp_build_cache", "lgp_build_clique_cache", "lgp_get_clique_plan",
-           "lgp_gather_features_clique", "lgp_get_cache_plan", "lgp_get_cache",
+           "lgp_gather_features_clique", "lgp_get_cache_plan", "lgp_get_cache", "lgp_get_cache_part", "lgp_reserve",
            "lgp_sample_khop", "lgp_build_blocks", "lgp_gather_features", "lgp_gather_features_static", "lgp_set_overlap", "lgp_workspace_bytes", "lgp_check", "lgp_set_profiling", "lgp_get_profile",
            "lgp_strerror", "lgp_last_error"]
 
@@ -95,6 +95,8 @@ def load_library():
     L.lgp_build_cache.argtypes = [vp, u64, u64, vp]
     L.lgp_get_cache_plan.argtypes = [vp, C.POINTER(CachePlan)]
     L.lgp_get_cache.argtypes = [vp, vp, vp, vp, vp, vp]
+    L.lgp_get_cache_part.argtypes = [vp, i32, i64, i64, vp]
+    L.lgp_reserve.argtypes = [vp, i32, vp, i32]
     L.lgp_build_clique_cache.argtypes = [vp, i32, vp, vp, u64, u64, vp]
     L.lgp_get_clique_plan.argtypes = [vp, i32, C.POINTER(CachePlan)]
     L.lgp_gather_features_clique.argtypes = [vp, i32, vp, i64, vp, vp, vp, vp]
@@ -386,6 +388,21 @@ class Context:
                                        t_indices.ctypes.data if contents else None, feat_ids.ctypes.data,
                                        feat_rows.ctypes.data if contents else None))
         return topo_ids, t_indptr, t_indices, feat_ids, feat_rows
+
+    def get_cache_part(self, which: int, first: int, count: int, out: np.ndarray | None = None) -> np.ndarray:
+        """which = 0: cached column ids [first, first + count) (int32); which = 1: cached feature rows of ranks
+        first .. first + count - 1 (uint8 [count, row_bytes]).  `out` may supply the destination."""
+        if out is None:
+            out = (np.empty(count, dtype=np.int32) if which == 0
+                   else np.empty((count, self.feat_dim * self.elem_bytes), dtype=np.uint8))
+        assert out.flags["C_CONTIGUOUS"] and out.nbytes >= count * (4 if which == 0 else self.feat_dim * self.elem_bytes)
+        self._ok(self._L.lgp_get_cache_part(self._h, which, int(first), int(count), out.ctypes.data))
+        return out
+
+    def reserve(self, max_seeds: int, fanouts):
+        """Size every per-batch scratch now; afterwards the per-batch calls never allocate or synchronise."""
+        fo = self._fanouts(fanouts)
+        self._ok(self._L.lgp_reserve(self._h, int(max_seeds), fo.ctypes.data, fo.size))
 
     def sample_khop(self, seeds: torch.Tensor, fanouts, rng_seed: int, out: SampleBuffers | None = None,
                     stream=None) -> SampleBuffers:

@@ -1,5 +1,6 @@
-// C ABI of liblegion_prep: argument checking, context state, launch sequencing.
-// No arithmetic of the method lives here; every step runs in the kernels.
+// C ABI of liblegion_prep: argument checking, context state, launch sequencing.  Every step of the
+// method runs in the kernels; the only arithmetic of the method done on the host is closed-form
+// sizing that needs no data -- Eq. 6's row count (budget / row bytes) and the alpha grid of Sec. 4.3.3.
 #include "common.hpp"
 
 #include <algorithm>
@@ -101,6 +102,7 @@ struct lgp_ctx {
 
   int profiling = 0;        // 0 off, 1 every per-batch kernel group, 2 the two row gathers only
   bool overlap = false;     // run the miss gather on its own stream beside the hit gather
+  bool reserved = false;    // lgp_reserve fixed the scratch sizes: nothing grows any more
   std::vector<EvPair> ev_used;
   std::vector<EvPair> ev_free;
 
@@ -321,6 +323,62 @@ int plan_core(lgp_ctx* c, uint64_t topo_budget, uint64_t feat_budget, CachePlan*
   return st;
 }
 
+// Scratch of the per-batch operators.  Each grows on demand (a growth step synchronises the stream and
+// reallocates) unless lgp_reserve fixed the sizes, after which a larger request is refused.
+int ensure_lists(lgp_ctx* c, int64_t n, hipStream_t s) {
+  if (n <= c->list_cap) return LGP_OK;
+  if (c->reserved) return fail(c, LGP_ECAPACITY, "more ids than lgp_reserve provided partition lists for");
+  LGP_HIP(c, hipStreamSynchronize(s));
+  LGP_HIP(c, hipStreamSynchronize(c->miss_stream));
+  if (c->lists) (void)hipFree(c->lists);
+  c->lists = nullptr;
+  c->list_cap = 0;
+  LGP_HIP(c, dev_alloc(&c->lists, size_t(n) * 6));
+  c->list_cap = n;
+  return LGP_OK;
+}
+
+int ensure_block_scratch(lgp_ctx* c, int32_t tables, int64_t tiles, hipStream_t s) {
+  if (c->pos_tables >= tables && c->tile_cap >= tiles) return LGP_OK;
+  if (c->reserved) return fail(c, LGP_ECAPACITY, "more hops or seeds than lgp_reserve provided graph-constructor scratch for");
+  LGP_HIP(c, hipStreamSynchronize(s));
+  if (c->pos_tables < tables) {
+    if (c->pos_table) (void)hipFree(c->pos_table);
+    c->pos_table = nullptr;
+    c->pos_tables = 0;
+    LGP_HIP(c, dev_alloc(&c->pos_table, size_t(tables) * size_t(c->g.num_vertices)));
+    c->pos_tables = tables;
+  }
+  if (c->tile_cap < tiles) {
+    if (c->tile_sums) (void)hipFree(c->tile_sums);
+    c->tile_sums = nullptr;
+    c->tile_cap = 0;
+    LGP_HIP(c, dev_alloc(&c->tile_sums, size_t(tiles)));
+    c->tile_cap = tiles;
+  }
+  return LGP_OK;
+}
+
+int ensure_presample_frontiers(lgp_ctx* c, const int64_t* need, int32_t n_hops, hipStream_t s) {
+  for (int h = 1; h < n_hops; ++h) {
+    if (c->hs_cap[h] >= need[h]) continue;
+    if (c->reserved) return fail(c, LGP_ECAPACITY, "larger pre-sampling batches than lgp_reserve provided frontiers for");
+    LGP_HIP(c, hipStreamSynchronize(s));
+    if (c->hs_frontier[h]) (void)hipFree(c->hs_frontier[h]);
+    c->hs_frontier[h] = nullptr;
+    c->hs_cap[h] = 0;
+    LGP_HIP(c, dev_alloc(&c->hs_frontier[h], size_t(need[h])));
+    c->hs_cap[h] = need[h];
+  }
+  return LGP_OK;
+}
+
+int64_t scan_tiles(const int64_t* cap, int32_t n_hops) {
+  int64_t tiles = 0;
+  for (int h = 0; h < n_hops; ++h) tiles += cap[h] / kScanTile + 1;
+  return tiles;
+}
+
 // member < 0: plain two-way extraction; member >= 0: three-way, as that member of the clique cache.
 // fixed != nullptr: the counters and lists live in that caller-provided block (kStaticHeadWords words, then
 // 2 * n_lists lists of fixed_cap entries); nothing is allocated, created or timed on this path.
@@ -366,14 +424,9 @@ int gather_core(lgp_ctx* c, int32_t member, const int32_t* ids, int64_t n_max, c
   } else {
     if (fixed) {
       if (n_max > fixed_cap) return fail(c, LGP_ECAPACITY, "n_max exceeds LGP_STATIC_GATHER_MAX_IDS");
-    } else if (n_max > c->list_cap) {              // scratch for the lists grows on demand
-      LGP_HIP(c, hipStreamSynchronize(s));
-      LGP_HIP(c, hipStreamSynchronize(c->miss_stream));
-      if (c->lists) (void)hipFree(c->lists);
-      c->lists = nullptr;
-      c->list_cap = 0;
-      LGP_HIP(c, dev_alloc(&c->lists, size_t(n_max) * 6));
-      c->list_cap = n_max;
+    } else {
+      const int st = ensure_lists(c, n_max, s);
+      if (st != LGP_OK) return st;
     }
     int32_t* const lists = fixed ? fixed + kStaticHeadWords : c->lists;
     const int64_t cap = fixed ? fixed_cap : c->list_cap;
@@ -587,16 +640,8 @@ int lgp_build_hotness(lgp_ctx* c, const int32_t* train_ids, int64_t n_train, int
   const int64_t V = c->g.num_vertices;
   int64_t need[LGP_MAX_HOPS + 1], gather_need;
   worst_case(c, std::min<int64_t>(batch, std::max<int64_t>(n_train, 1)), fanouts, n_hops, need, &gather_need);
-  for (int h = 1; h < n_hops; ++h) {
-    if (c->hs_cap[h] < need[h]) {
-      LGP_HIP(c, hipStreamSynchronize(s));
-      if (c->hs_frontier[h]) (void)hipFree(c->hs_frontier[h]);
-      c->hs_frontier[h] = nullptr;
-      c->hs_cap[h] = 0;
-      LGP_HIP(c, dev_alloc(&c->hs_frontier[h], size_t(need[h])));
-      c->hs_cap[h] = need[h];
-    }
-  }
+  st = ensure_presample_frontiers(c, need, n_hops, s);
+  if (st != LGP_OK) return st;
   launch_fill_i32(c->di, reinterpret_cast<int32_t*>(c->topo_hot), V, 0, s);
   launch_fill_i32(c->di, reinterpret_cast<int32_t*>(c->feat_hot), V, 0, s);
   launch_fill_i32(c->di, reinterpret_cast<int32_t*>(c->hs_expansions), 2, 0, s);
@@ -969,25 +1014,8 @@ int lgp_get_cache(lgp_ctx* c, int32_t* topo_ids, int64_t* t_indptr, int32_t* t_i
   if (feat_ids && p.n_feat)
     LGP_HIP(c, hipMemcpy(feat_ids, c->order_f, sizeof(int32_t) * size_t(p.n_feat), hipMemcpyDeviceToHost));
   if (feat_rows && p.n_feat) {
-    if (!c->fc_identity) {
-      LGP_HIP(c, hipMemcpy(feat_rows, c->fc, size_t(p.feat_bytes), hipMemcpyDeviceToHost));
-    } else {
-      // the cache sits in vertex order; hand it out in rank order like any other cache
-      const int64_t chunk = std::max<int64_t>(1, std::min<int64_t>(p.n_feat, (int64_t(256) << 20) / c->row_bytes));
-      void* tmp = nullptr;
-      LGP_HIP(c, hipMalloc(&tmp, size_t(chunk * c->row_bytes)));
-      hipError_t e = hipSuccess;
-      for (int64_t lo = 0; lo < p.n_feat && e == hipSuccess; lo += chunk) {
-        const int64_t n = std::min(chunk, p.n_feat - lo);
-        launch_gather_rows(c->di, c->fc, tmp, c->row_bytes, nullptr, c->order_f + lo, n, nullptr, false, nullptr);
-        e = hipGetLastError();
-        if (e == hipSuccess)
-          e = hipMemcpy(static_cast<char*>(feat_rows) + lo * c->row_bytes, tmp, size_t(n * c->row_bytes),
-                        hipMemcpyDeviceToHost);
-      }
-      (void)hipFree(tmp);
-      if (e != hipSuccess) return fail_hip(c, e, "reading the feature cache back");
-    }
+    const int st = lgp_get_cache_part(c, 1, 0, p.n_feat, feat_rows);
+    if (st != LGP_OK) return st;
   }
   return LGP_OK;
 }
@@ -1062,23 +1090,8 @@ int lgp_build_blocks(lgp_ctx* c, const int32_t* seeds, int32_t n_seeds, const in
     tiles += a.cap[h] / kScanTile + 1;
   }
   // scratch: one position table per list (the extracted ids and every frontier after the seeds) and the scan tiles
-  if (c->pos_tables < n_hops + 1 || c->tile_cap < tiles) {
-    LGP_HIP(c, hipStreamSynchronize(s));
-    if (c->pos_tables < n_hops + 1) {
-      if (c->pos_table) (void)hipFree(c->pos_table);
-      c->pos_table = nullptr;
-      c->pos_tables = 0;
-      LGP_HIP(c, dev_alloc(&c->pos_table, size_t(n_hops + 1) * size_t(c->g.num_vertices)));
-      c->pos_tables = n_hops + 1;
-    }
-    if (c->tile_cap < tiles) {
-      if (c->tile_sums) (void)hipFree(c->tile_sums);
-      c->tile_sums = nullptr;
-      c->tile_cap = 0;
-      LGP_HIP(c, dev_alloc(&c->tile_sums, size_t(tiles)));
-      c->tile_cap = tiles;
-    }
-  }
+  st = ensure_block_scratch(c, n_hops + 1, tiles, s);
+  if (st != LGP_OK) return st;
   a.table = c->pos_table;
   a.tile_sums = c->tile_sums;
   launch_build_blocks(c->di, a, s);
@@ -1108,6 +1121,59 @@ int lgp_gather_features_clique(lgp_ctx* c, int32_t member, const int32_t* ids, i
   if (c->clique_k == 0) return fail(c, LGP_ESTATE, "no clique cache: call lgp_build_clique_cache first");
   if (member < 0 || member >= c->clique_k) return fail(c, LGP_EINVAL, "member outside the clique");
   return gather_core(c, member, ids, n_max, n_dev, out, stats, stream);
+}
+
+int lgp_reserve(lgp_ctx* c, int32_t max_seeds, const int32_t* fanouts, int32_t n_hops) {
+  if (!c) return LGP_EINVAL;
+  if (max_seeds < 0) return fail(c, LGP_EINVAL, "max_seeds is negative");
+  int st = check_fanouts(c, fanouts, n_hops);
+  if (st != LGP_OK) return st;
+  LGP_HIP(c, hipSetDevice(c->di.device));
+  LGP_HIP(c, hipDeviceSynchronize());
+  int64_t need[LGP_MAX_HOPS + 1], gather_need;
+  worst_case(c, max_seeds, fanouts, n_hops, need, &gather_need);
+  c->reserved = false;
+  if ((st = ensure_lists(c, gather_need, nullptr)) != LGP_OK) return st;
+  if ((st = ensure_block_scratch(c, n_hops + 1, scan_tiles(need, n_hops), nullptr)) != LGP_OK) return st;
+  if ((st = ensure_presample_frontiers(c, need, n_hops, nullptr)) != LGP_OK) return st;
+  c->reserved = true;
+  return LGP_OK;
+}
+
+int lgp_get_cache_part(lgp_ctx* c, int32_t which, int64_t first, int64_t count, void* dst) {
+  if (!c) return LGP_EINVAL;
+  if (first < 0 || count < 0 || (count > 0 && !dst)) return fail(c, LGP_EINVAL, "first / count / dst");
+  LGP_HIP(c, hipSetDevice(c->di.device));
+  LGP_HIP(c, hipDeviceSynchronize());
+  const CachePlan& p = c->plan;
+  if (count == 0) return LGP_OK;
+  if (which == 0) {
+    if (first + count > p.topo_edges) return fail(c, LGP_EINVAL, "range beyond the cached column ids");
+    LGP_HIP(c, hipMemcpy(dst, c->t_indices + first, sizeof(int32_t) * size_t(count), hipMemcpyDeviceToHost));
+    return LGP_OK;
+  }
+  if (which != 1) return fail(c, LGP_EINVAL, "which must be 0 (column ids) or 1 (feature rows)");
+  if (first + count > p.n_feat) return fail(c, LGP_EINVAL, "range beyond the cached feature rows");
+  if (!c->fc_identity) {
+    LGP_HIP(c, hipMemcpy(dst, static_cast<const char*>(c->fc) + first * c->row_bytes, size_t(count * c->row_bytes),
+                         hipMemcpyDeviceToHost));
+    return LGP_OK;
+  }
+  // the cache sits in vertex order; hand the rows out in rank order like any other cache
+  const int64_t chunk = std::max<int64_t>(1, std::min<int64_t>(count, (int64_t(256) << 20) / c->row_bytes));
+  void* tmp = nullptr;
+  LGP_HIP(c, hipMalloc(&tmp, size_t(chunk * c->row_bytes)));
+  hipError_t e = hipSuccess;
+  for (int64_t lo = 0; lo < count && e == hipSuccess; lo += chunk) {
+    const int64_t n = std::min(chunk, count - lo);
+    launch_gather_rows(c->di, c->fc, tmp, c->row_bytes, nullptr, c->order_f + first + lo, n, nullptr, false, nullptr);
+    e = hipGetLastError();
+    if (e == hipSuccess)
+      e = hipMemcpy(static_cast<char*>(dst) + lo * c->row_bytes, tmp, size_t(n * c->row_bytes), hipMemcpyDeviceToHost);
+  }
+  (void)hipFree(tmp);
+  if (e != hipSuccess) return fail_hip(c, e, "reading the feature cache back");
+  return LGP_OK;
 }
 
 int lgp_workspace_bytes(const lgp_ctx* c, int32_t max_seeds, const int32_t* fanouts, int32_t n_hops, size_t* fixed,
