@@ -61,6 +61,8 @@ def _load():
         L.orc_block_of_hop.restype = None
         L.orc_feature_rows.argtypes = [vp, i32, vp]
         L.orc_feature_rows.restype = None
+        L.orc_hop_order.argtypes = [vp, i64, vp, vp]
+        L.orc_hop_order.restype = i64
         L.orc_batch_free.argtypes = [vp]
         L.orc_batch_free.restype = None
         L.orc_build_hotness.argtypes = [gp, vp, i64, i32, vp, i32, u64, i64, vp, vp]
@@ -154,6 +156,8 @@ class Batch:
     blk_indptr: list = field(default_factory=list)   # per hop: int64[len(frontier[h]) + 1]
     blk_src: list = field(default_factory=list)      # per hop: int32[edges], positions inside frontier[h + 1]
     feat_row: list = field(default_factory=list)     # per frontier: positions inside gather_ids
+    hop_order: np.ndarray = None                     # extraction order of the intra-batch pipeline
+    hop_seg: np.ndarray = None                       # its groups: [seg[h], seg[h + 1]) = seeds (h = 0), hop h's new vertices
 
 
 class Oracle:
@@ -192,6 +196,10 @@ class Oracle:
             n_last = int(self._L.orc_batch_frontier_size(h, fo.size))
             b.frontier.append(_copy(self._L.orc_batch_frontier(h, fo.size), n_last))
             b.gather_ids = _copy(self._L.orc_batch_gather_ids(h), int(self._L.orc_batch_gather_size(h)))
+            b.hop_seg = np.zeros(fo.size + 2, dtype=np.int64)
+            total = int(self._L.orc_hop_order(h, self.V, None, _p(b.hop_seg)))
+            b.hop_order = np.empty(total, dtype=np.int32)
+            self._L.orc_hop_order(h, self.V, _p(b.hop_order) if total else None, _p(b.hop_seg))
             if blocks:
                 for hop in range(fo.size):
                     n = b.frontier[hop].size

@@ -32,6 +32,9 @@
 //     whose features are extracted is the ascending sorted union of the seeds
 //     and all sampled neighbours.
 //
+//   * extraction order of the intra-batch pipeline (Sec. 5; order not stated): seeds as
+//     given, then per hop the vertices first reached by that hop, ascending.
+//
 //   * cache plan search (Sec. 4.3): for alpha = 0, 1/(n-1), ..., 1 the topology cache gets
 //     m_T = floor(B * alpha) bytes and the feature cache B - m_T; N_total = N_T + N_F with
 //     Eq. 3-8, the plan with the smallest N_total wins (paper silent on ties: smallest
@@ -254,6 +257,38 @@ void orc_feature_rows(const void* handle, int32_t hop, int32_t* feat_row) {
   for (size_t i = 0; i < b.frontier[hop].size(); ++i)
     feat_row[i] = static_cast<int32_t>(std::lower_bound(b.gather_ids.begin(), b.gather_ids.end(), b.frontier[hop][i]) -
                                        b.gather_ids.begin());
+}
+
+// --- extraction order of the intra-batch pipeline (Sec. 5) ------------------
+// Sec. 5: within one batch, sampling and graph construction can run beside feature
+// extraction.  The extractor can only run ahead of the sampler if it takes the vertices in
+// the order in which the sampler reaches them (paper silent on that order; reading): first
+// the seeds as given, then, hop after hop, the vertices that hop reaches for the first time
+// -- the members of frontier h (h = 1 .. n_hops) that are neither seeds nor members of an
+// earlier frontier -- each group in ascending order.  seg (n_hops + 2 entries) delimits the
+// groups: seg[0] = 0, seg[1] = number of seeds, seg[h + 1] = end of hop h's group.  Returns
+// the total; call with out == nullptr to learn it.
+int64_t orc_hop_order(const void* handle, int64_t num_vertices, int32_t* out, int64_t* seg) {
+  const Batch& b = *static_cast<const Batch*>(handle);
+  std::vector<uint8_t> seen(static_cast<size_t>(num_vertices), 0);
+  int64_t at = 0;
+  seg[0] = 0;
+  for (int32_t v : b.frontier[0]) {            // the seed list, duplicates and all
+    if (out) out[at] = v;
+    ++at;
+    seen[v] = 1;
+  }
+  seg[1] = at;
+  for (int32_t h = 1; h <= b.n_hops; ++h) {
+    for (int32_t v : b.frontier[h]) {          // ascending by construction
+      if (seen[v]) continue;
+      seen[v] = 1;
+      if (out) out[at] = v;
+      ++at;
+    }
+    seg[h + 1] = at;
+  }
+  return at;
 }
 
 // --- pre-sampling hotness (Sec. 4.2.2, S1) ---------------------------------

@@ -163,3 +163,40 @@ def test_int64_offsets_give_same_result(oracle_mod):
     a = oracle_mod.Oracle(indptr, indices).sample_khop(np.arange(100, dtype=np.int32), [10, 5], 8)
     b = oracle_mod.Oracle(indptr.astype(np.int64), indices).sample_khop(np.arange(100, dtype=np.int32), [10, 5], 8)
     assert all((x == y).all() for x, y in zip(a.nbr + [a.gather_ids], b.nbr + [b.gather_ids]))
+
+
+def test_hop_order_is_first_reach_order():
+    """Extraction order of the intra-batch pipeline: seeds as given, then per hop the vertices that hop reaches for
+    the first time, ascending -- rebuilt here from the oracle's own frontiers with Python sets, plus what must hold
+    whatever the order: it is a permutation of the ascending extraction set, every vertex sits in the group of the
+    first hop whose samples contain it, and a hop that reaches nothing new has an empty group."""
+    import oracle
+    spec = datagen.TINY
+    indptr, indices = datagen.make_graph(spec)
+    orc = oracle.Oracle(indptr, indices)
+    seeds = datagen.make_tablet(spec)[:300]
+    for fanouts in ((10, 5), (3, 3, 3), (25,)):
+        b = orc.sample_khop(seeds, fanouts, 99)
+        seen, want, seg = set(seeds.tolist()), list(seeds.tolist()), [0, len(seeds)]
+        for h in range(1, len(fanouts) + 1):
+            new = sorted(set(b.frontier[h].tolist()) - seen)
+            want += new
+            seen |= set(new)
+            seg.append(len(want))
+        assert b.hop_order.tolist() == want and b.hop_seg.tolist() == seg
+        assert sorted(b.hop_order.tolist()) == b.gather_ids.tolist()          # same set as the ascending list
+        first_hop = {}
+        for h in range(len(fanouts)):
+            for u in b.nbr[h][b.nbr[h] >= 0].tolist():
+                first_hop.setdefault(u, h + 1)
+        for g in range(1, len(seg) - 1):
+            for u in b.hop_order[seg[g]:seg[g + 1]].tolist():
+                assert first_hop[u] == g and u not in set(seeds.tolist())
+    # hand-worked: path 0 -> 1 -> 2 -> 0 with a chord 0 -> 2; seeds [2, 0]
+    ip = np.array([0, 2, 3, 4], dtype=np.int32)
+    ix = np.array([1, 2, 2, 0], dtype=np.int32)
+    b = oracle.Oracle(ip, ix).sample_khop(np.array([2, 0], dtype=np.int32), (2, 2), 1)
+    assert b.frontier[1].tolist() == [0, 1, 2] and b.hop_order.tolist() == [2, 0, 1] and b.hop_seg.tolist() == [0, 2, 3, 3]
+    # duplicate seeds stay as given
+    b = oracle.Oracle(ip, ix).sample_khop(np.array([1, 1], dtype=np.int32), (1,), 1)
+    assert b.hop_order.tolist() == [1, 1, 2] and b.hop_seg.tolist() == [0, 2, 3]
