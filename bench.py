@@ -44,7 +44,7 @@ TRAFFIC_JSON = os.path.join(ROOT, "profiles", "hbm_traffic.json")
 
 
 def measured_traffic(key: str):
-    """The profile record of one launch shape ("share", "wide@0.25", ...), or (None, why)."""
+    """The profile record of one launch shape ("share@topo1,feat1", "wide@topo1,feat0.25", ...), or (None, why)."""
     try:
         with open(TRAFFIC_JSON) as f:
             table = json.load(f)
@@ -128,7 +128,8 @@ def timed_regions(fn, first: int, steps: int, reps: int):
 
 
 def measure(inp: Inputs, steps: int, warmup: int, reps: int, topo_frac=None, feat_frac=None, cache_bytes: int = 0,
-            alpha=None, overlap: bool = False, extras: bool = False, clique_k: int = 0, copy_calibration: bool = False):
+            alpha=None, overlap: bool = False, extras: bool = False, intra: bool = True, clique_k: int = 0,
+            copy_calibration: bool = False):
     """Build the caches for the given ratios and time the step.  Returns one record."""
     import numpy as np
     import torch
@@ -215,9 +216,8 @@ def measure(inp: Inputs, steps: int, warmup: int, reps: int, topo_frac=None, fea
     st = stats[warmup:].cpu().numpy().astype(np.int64)
     hit_rows, miss_rows = int(st[:, 0].sum()), int(st[:, 1].sum())
     gathered = hit_rows + miss_rows
-    shape_key = inp.spec.name + ("" if (topo_frac is None and feat_frac is None and not cache_bytes)
-                                 else f"@topo{spec.topo_frac:g},feat{spec.feat_frac:g}" if not cache_bytes
-                                 else f"@B{cache_bytes}")
+    shape_key = (f"{inp.spec.name}@B{cache_bytes}" if cache_bytes
+                 else f"{inp.spec.name}@topo{spec.topo_frac:g},feat{spec.feat_frac:g}")
     prof_rec, prof_why = measured_traffic(shape_key)
 
     # algorithmic bytes of one hit-gather launch: each hit row is read once and written once,
@@ -287,6 +287,26 @@ def measure(inp: Inputs, steps: int, warmup: int, reps: int, topo_frac=None, fea
         "setup_s": {"generate": round(inp.t_gen, 2), "build_hotness": round(inp.t_hot, 3),
                     "build_cache": round(t_cache, 3)},
     }
+    # Secondary figure: the intra-batch pipeline of Sec. 5 -- the same batches through lgp_sample_extract, which
+    # extracts the seeds' rows while hop 0 is sampled and every hop's newly reached rows while the next hop is
+    # sampled (rows come out in first-reach order instead of ascending id order).
+    if intra:
+        groups = torch.zeros(L + 2, dtype=torch.int32, device="cuda")
+        istats = torch.zeros((warmup + steps, 2), dtype=torch.int32, device="cuda")
+
+        def istep(i: int):
+            ctx.sample_extract(inp.seeds(i), spec.fanouts, spec.base_seed + i, buf, rows, groups, istats[i])
+
+        for i in range(warmup):
+            istep(i)
+        t_intra = timed_regions(istep, warmup, steps, 1)[0]
+        ctx.check()
+        assert torch.equal(istats[warmup:].cpu(), stats[warmup:warmup + steps].cpu()), "intra-batch pipeline diverged"
+        rec["intra_batch_pipeline"] = {
+            "value": round(steps * spec.batch / t_intra, 1), "unit": "seeds/s",
+            "ms_per_step": round(t_intra * 1e3 / steps, 4),
+            "how": "lgp_sample_extract: extraction of the seeds' rows beside hop 0, of each hop's newly reached rows "
+                   "beside the next hop, on a second stream"}
     if extras:
         rec.update(secondary_figures(inp, spec, plan, buf, rows, stats, steps, warmup, ms_per_step, overlap, step))
     if clique_k > 0:
@@ -592,7 +612,8 @@ def main() -> int:
         inp = Inputs(head_spec)
     head = measure(inp, args.steps, args.warmup, args.reps, topo_frac=args.topo_frac, feat_frac=args.feat_frac,
                    cache_bytes=args.cache_bytes, alpha=args.alpha, overlap=args.overlap,
-                   extras=not args.no_pipeline, clique_k=args.clique, copy_calibration=args.copy_calibration)
+                   extras=not args.no_pipeline, intra=not args.no_pipeline, clique_k=args.clique,
+                   copy_calibration=args.copy_calibration)
     cpu = cpu_all = None
     if not args.no_cpu_baseline:
         cpu, cpu_all = cpu_baseline(inp, args.warmup, args.cpu_batches or args.steps)
@@ -607,7 +628,7 @@ def main() -> int:
                 continue
             try:
                 other = Inputs(datagen.WORKLOADS[name])
-                configs[name] = measure(other, k, w, r)
+                configs[name] = measure(other, k, w, r, intra=not args.no_pipeline)
                 other.close()
                 del other
             except Exception as e:
@@ -618,7 +639,7 @@ def main() -> int:
             try:
                 other = Inputs(datagen.WORKLOADS["wide"])
                 for frac in (0.0, 0.10, 0.25, 0.50, 1.0):
-                    configs[f"wide@feat{frac:g}"] = measure(other, k, w, r, feat_frac=frac)
+                    configs[f"wide@feat{frac:g}"] = measure(other, k, w, r, feat_frac=frac, intra=not args.no_pipeline)
                 other.close()
                 del other
             except Exception as e:
@@ -638,7 +659,8 @@ def main() -> int:
         "roofline_sampler": head["roofline_sampler"], "cpu_baseline": cpu, "cpu_baseline_all_cores": cpu_all,
         "per_step": head["per_step"], "setup_s": head["setup_s"],
     }
-    for key in ("overlapped", "pipelined", "sampling_server", "graph_replay", "graph_constructor_ms", "clique"):
+    for key in ("intra_batch_pipeline", "overlapped", "pipelined", "sampling_server", "graph_replay",
+                "graph_constructor_ms", "clique"):
         line[key] = head.get(key)
     line["configs"] = configs
     line["bench_wall_s"] = round(time.time() - t_start, 1)

@@ -258,6 +258,27 @@ int lgp_get_cache_part(lgp_ctx* ctx, int32_t which, int64_t first, int64_t count
 int lgp_sample_khop(lgp_ctx* ctx, const int32_t* seeds, int32_t n_seeds, const int32_t* fanouts, int32_t n_hops,
                     uint64_t rng_seed, const lgp_sample_out* out, void* stream);
 
+/* One mini-batch through the intra-batch pipeline of Sec. 5 ("for the same batch, graph sampling ... can be
+ * overlapped with feature extraction"): lgp_sample_khop and lgp_gather_features in one call, with the
+ * extraction running on a stream of the library's own beside the sampling.  That is only possible if rows are
+ * extracted in the order in which the sampler reaches their vertices, so out->gather_ids is not the ascending
+ * list here but the listing
+ *     seeds as given | vertices first reached by hop 0, ascending | ... | first reached by hop n_hops-1, ascending
+ * (a vertex is "first reached" by a hop if it is among that hop's samples and is neither a seed nor among the
+ * samples of an earlier hop; as a set the listing equals lgp_sample_khop's gather_ids).  The seeds' rows are
+ * extracted while hop 0 is sampled, hop h's group while hop h+1 is sampled, the last group after the last hop.
+ * Everything else in `out` is what lgp_sample_khop writes (frontiers, nbr, cnt, counts; *out->n_gather = length
+ * of the listing).  rows [device] receives the feature row of gather_ids[i] at row i, like lgp_gather_features;
+ * groups [device int32[n_hops + 2], may be NULL] receives the group bounds (groups[0] = 0, groups[1] = n_seeds,
+ * group g = [groups[g], groups[g+1])); stats [device int32[2], may be NULL] = {n_hit, n_miss} over all groups.
+ * Seeds must be distinct (a repeated seed is listed, and its row extracted, once per occurrence;
+ * out->gather_cap must also be >= n_seeds).  `stream` waits for the extraction before later work on it runs.
+ * lgp_build_blocks accepts the result (its feat_row then points into this listing).  Not to be overlapped with
+ * lgp_sample_khop, lgp_gather_features or another lgp_sample_extract on the same context. */
+int lgp_sample_extract(lgp_ctx* ctx, const int32_t* seeds, int32_t n_seeds, const int32_t* fanouts, int32_t n_hops,
+                       uint64_t rng_seed, const lgp_sample_out* out, void* rows, int32_t* groups, int32_t* stats,
+                       void* stream);
+
 /* Graph constructor (Sec. 5, operator 4: "generating the subgraph based on the sampled
  * results").  Takes the buffers a finished lgp_sample_khop call filled (same seeds, fanouts
  * and `sampled`, with sampled->frontier[n_hops] given) and writes, per hop h, a bipartite

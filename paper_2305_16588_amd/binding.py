@@ -62,7 +62,7 @@ class Profile(C.Structure):
 EXPORTS = ["lgp_host_alloc", "lgp_host_free", "lgp_shuffle_tablet", "lgp_create", "lgp_destroy", "lgp_build_hotness", "lgp_get_presample_stats", "lgp_get_hotness",
            "lgp_set_hotness", "lgp_plan_cache", "lgp_search_cache_plan", "lgp_cslp", "lgp_build_cache", "lgp_build_clique_cache", "lgp_get_clique_plan",
            "lgp_gather_features_clique", "lgp_get_cache_plan", "lgp_get_cache", "lgp_get_cache_part", "lgp_reserve",
-           "lgp_sample_khop", "lgp_build_blocks", "lgp_gather_features", "lgp_gather_features_static", "lgp_set_overlap", "lgp_workspace_bytes", "lgp_check", "lgp_set_profiling", "lgp_get_profile",
+           "lgp_sample_khop", "lgp_sample_extract", "lgp_build_blocks", "lgp_gather_features", "lgp_gather_features_static", "lgp_set_overlap", "lgp_workspace_bytes", "lgp_check", "lgp_set_profiling", "lgp_get_profile",
            "lgp_strerror", "lgp_last_error"]
 
 _lib = None
@@ -101,6 +101,7 @@ def load_library():
     L.lgp_get_clique_plan.argtypes = [vp, i32, C.POINTER(CachePlan)]
     L.lgp_gather_features_clique.argtypes = [vp, i32, vp, i64, vp, vp, vp, vp]
     L.lgp_sample_khop.argtypes = [vp, vp, i32, vp, i32, u64, C.POINTER(_SampleOut), vp]
+    L.lgp_sample_extract.argtypes = [vp, vp, i32, vp, i32, u64, C.POINTER(_SampleOut), vp, vp, vp, vp]
     L.lgp_build_blocks.argtypes = [vp, vp, i32, vp, i32, C.POINTER(_SampleOut), C.POINTER(_BlocksOut), vp]
     L.lgp_gather_features.argtypes = [vp, vp, i64, vp, vp, vp, vp]
     L.lgp_gather_features_static.argtypes = [vp, vp, i64, vp, vp, vp, vp]
@@ -412,6 +413,19 @@ class Context:
             out = SampleBuffers(self.num_vertices, seeds.numel(), fo.tolist(), self.device)
         self._ok(self._L.lgp_sample_khop(self._h, seeds.data_ptr(), seeds.numel(), fo.ctypes.data, fo.size,
                                          rng_seed & (2**64 - 1), C.byref(out.c_struct), _stream_ptr(stream)))
+        return out
+
+    def sample_extract(self, seeds: torch.Tensor, fanouts, rng_seed: int, out: SampleBuffers, rows: torch.Tensor,
+                       groups: torch.Tensor | None = None, stats: torch.Tensor | None = None, stream=None):
+        """sample_khop + gather_features of one batch with the extraction overlapped hop by hop; out.gather_ids
+        receives the listing (seeds, then per hop the vertices it reached first), rows its feature rows."""
+        assert seeds.is_cuda and seeds.dtype == torch.int32 and seeds.is_contiguous()
+        assert rows.is_cuda and rows.is_contiguous() and rows.numel() * rows.element_size() >= out.gather_cap * self.feat_dim * self.elem_bytes
+        fo = self._fanouts(fanouts)
+        self._ok(self._L.lgp_sample_extract(self._h, seeds.data_ptr(), seeds.numel(), fo.ctypes.data, fo.size,
+                                            rng_seed & (2**64 - 1), C.byref(out.c_struct), rows.data_ptr(),
+                                            None if groups is None else groups.data_ptr(),
+                                            None if stats is None else stats.data_ptr(), _stream_ptr(stream)))
         return out
 
     def build_blocks(self, seeds: torch.Tensor, fanouts, sample: SampleBuffers, out: BlockBuffers | None = None,

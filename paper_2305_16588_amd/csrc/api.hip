@@ -100,6 +100,15 @@ struct lgp_ctx {
   hipStream_t miss_stream = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
 
+  // intra-batch pipeline (lgp_sample_extract): the extractor's stream, one event per group of rows,
+  // the groups' bounds and their hit / miss counts
+  hipStream_t extract_stream = nullptr;
+  hipEvent_t ev_group[LGP_MAX_HOPS + 2] = {};
+  hipEvent_t ev_extracted = nullptr;
+  int32_t* seg = nullptr;            // int32[LGP_MAX_HOPS + 2]
+  int32_t* seg_counters = nullptr;   // int32[(LGP_MAX_HOPS + 1) * 3]
+  int32_t* new_counts = nullptr;     // per compaction chunk: vertices reached first by the hop
+
   int profiling = 0;        // 0 off, 1 every per-batch kernel group, 2 the two row gathers only
   bool overlap = false;     // run the miss gather on its own stream beside the hit gather
   bool reserved = false;    // lgp_reserve fixed the scratch sizes: nothing grows any more
@@ -382,8 +391,11 @@ int64_t scan_tiles(const int64_t* cap, int32_t n_hops) {
 // member < 0: plain two-way extraction; member >= 0: three-way, as that member of the clique cache.
 // fixed != nullptr: the counters and lists live in that caller-provided block (kStaticHeadWords words, then
 // 2 * n_lists lists of fixed_cap entries); nothing is allocated, created or timed on this path.
+// window != nullptr (device {begin, end}): only those entries of ids are extracted, into the output rows of the
+// same numbers; window_items bounds their count (for sizing the grids).
 int gather_core(lgp_ctx* c, int32_t member, const int32_t* ids, int64_t n_max, const int32_t* n_dev, void* out,
-                       int32_t* stats, void* stream, int32_t* fixed = nullptr, int64_t fixed_cap = 0) {
+                       int32_t* stats, void* stream, int32_t* fixed = nullptr, int64_t fixed_cap = 0,
+                       const int32_t* window = nullptr, int64_t window_items = 0) {
   if (n_max < 0 || (n_max > 0 && (!ids || !out))) return fail(c, LGP_EINVAL, "ids / out / n_max");
   if (!c->g.features) return fail(c, LGP_ESTATE, "the graph was created without a feature table");
   if (n_max >= (int64_t(1) << 31)) return fail(c, LGP_EUNSUPPORTED, "more than 2^31 - 1 rows in one call");
@@ -413,13 +425,14 @@ int gather_core(lgp_ctx* c, int32_t member, const int32_t* ids, int64_t n_max, c
     // every row is cached: no partition, the id list is looked up by the gather itself
     ev = prof_pair(c, PK_HIT);
     launch_gather_rows(c->di, c->fc, out, c->row_bytes, nullptr, ids, n_max, n_dev, false, s,
-                       DirectIds{c->fc_identity ? nullptr : c->f_remap, V, counters, 0, c->d_err}, ev.a, ev.b);
+                       DirectIds{c->fc_identity ? nullptr : c->f_remap, V, counters, 0, c->d_err, window}, ev.a, ev.b,
+                       false, window_items);
     prof_keep(c, ev);
   } else if (!three && c->plan.n_feat == 0) {
     // nothing is cached: every id is its own source row in CPU memory
     ev = prof_pair(c, PK_MISS);
     launch_gather_rows(c->di, c->g.features, out, c->row_bytes, nullptr, ids, n_max, n_dev, true, s,
-                       DirectIds{nullptr, V, counters, 1, c->d_err}, ev.a, ev.b);
+                       DirectIds{nullptr, V, counters, 1, c->d_err, window}, ev.a, ev.b, false, window_items);
     prof_keep(c, ev);
   } else {
     if (fixed) {
@@ -437,7 +450,7 @@ int gather_core(lgp_ctx* c, int32_t member, const int32_t* ids, int64_t n_max, c
     ev = prof_begin(c, PK_PARTITION, s);
     launch_partition(c->di, ids, n_max, n_dev, c->f_remap, V, L, three ? 3 : 2,
                      three ? int32_t(c->clique_fn[member]) : 0, three ? int32_t(c->clique_fn[member + 1]) : 0, counters,
-                     c->d_err, s);
+                     c->d_err, s, window, window_items);
     prof_end(c, ev, s);
     // Hits first (HBM -> HBM, short), then misses (PCIe, long).  With overlap enabled the
     // misses run on a second stream beside the hits and rejoin `s` afterwards.
@@ -447,20 +460,21 @@ int gather_core(lgp_ctx* c, int32_t member, const int32_t* ids, int64_t n_max, c
       LGP_HIP(c, hipEventRecord(c->ev_fork, s));
       LGP_HIP(c, hipStreamWaitEvent(ms, c->ev_fork, 0));
     }
-    const DirectIds listed{nullptr, 0, nullptr, 0, nullptr};
+    const DirectIds listed{nullptr, 0, nullptr, 0, nullptr, nullptr};
+    const int64_t items = (window && window_items > 0 && window_items < n_max) ? window_items : n_max;
     ev = prof_pair(c, PK_HIT);
     launch_gather_rows(c->di, c->fc, out, c->row_bytes, L.row[0], L.src[0], n_max, counters, false, s, listed, ev.a,
-                       ev.b, c->overlap);
+                       ev.b, c->overlap, items);
     prof_keep(c, ev);
     if (three) {   // rows a peer caches: on this one device a second HBM gather, from the peers' regions
       ev = prof_pair(c, PK_HIT);
       launch_gather_rows(c->di, c->fc, out, c->row_bytes, L.row[2], L.src[2], n_max, counters + 2, false, s, listed,
-                         ev.a, ev.b, c->overlap);
+                         ev.a, ev.b, c->overlap, items);
       prof_keep(c, ev);
     }
     ev = prof_pair(c, PK_MISS);
     launch_gather_rows(c->di, c->g.features, out, c->row_bytes, L.row[1], L.src[1], n_max, counters + 1, true, ms,
-                       listed, ev.a, ev.b);
+                       listed, ev.a, ev.b, false, items);
     prof_keep(c, ev);
     if (c->overlap) {
       LGP_HIP(c, hipEventRecord(c->ev_join, ms));
@@ -581,6 +595,9 @@ int lgp_create(const lgp_graph* g, int device, lgp_ctx** out) {
   step(dev_alloc(&c->counters, 3));
   step(dev_alloc(&c->hs_n, LGP_MAX_HOPS + 1));
   step(dev_alloc(&c->hs_expansions, 1));
+  step(dev_alloc(&c->seg, LGP_MAX_HOPS + 2));
+  step(dev_alloc(&c->seg_counters, (LGP_MAX_HOPS + 1) * 3));
+  step(dev_alloc(&c->new_counts, size_t(c->n_chunks)));
   if (e == hipSuccess) e = hipMemset(c->f_remap, 0xff, sizeof(int32_t) * size_t(V));
   if (e == hipSuccess) e = hipMemset(c->topo_hot, 0, sizeof(uint32_t) * size_t(V));
   if (e == hipSuccess) e = hipMemset(c->feat_hot, 0, sizeof(uint32_t) * size_t(V));
@@ -592,6 +609,10 @@ int lgp_create(const lgp_graph* g, int device, lgp_ctx** out) {
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->miss_stream, hipStreamNonBlocking);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming);
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->extract_stream, hipStreamNonBlocking);
+  for (int k = 0; k < LGP_MAX_HOPS + 2 && e == hipSuccess; ++k)
+    e = hipEventCreateWithFlags(&c->ev_group[k], hipEventDisableTiming);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_extracted, hipEventDisableTiming);
   if (e == hipSuccess) {
     launch_init_row_table(c->di, c->g.indptr, c->g.indptr_bytes, V, c->row_tab, nullptr);
     e = hipGetLastError();
@@ -611,7 +632,8 @@ int lgp_destroy(lgp_ctx* c) {
   (void)hipDeviceSynchronize();
   free_cache(c);
   void* ptrs[] = {c->row_tab, c->f_remap, c->topo_hot, c->feat_hot, c->fbits, c->gbits, c->chunk_counts,
-                  c->d_err,   c->counters, c->order_t, c->order_f,  c->lists, c->hs_n, c->pos_table, c->tile_sums, c->hs_expansions};
+                  c->d_err,   c->counters, c->order_t, c->order_f,  c->lists, c->hs_n, c->pos_table, c->tile_sums, c->hs_expansions,
+                  c->seg, c->seg_counters, c->new_counts};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   for (int h = 0; h < LGP_MAX_HOPS; ++h)
@@ -624,6 +646,10 @@ int lgp_destroy(lgp_ctx* c) {
   if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
   if (c->ev_join) (void)hipEventDestroy(c->ev_join);
   if (c->miss_stream) (void)hipStreamDestroy(c->miss_stream);
+  for (hipEvent_t ev : c->ev_group)
+    if (ev) (void)hipEventDestroy(ev);
+  if (c->ev_extracted) (void)hipEventDestroy(c->ev_extracted);
+  if (c->extract_stream) (void)hipStreamDestroy(c->extract_stream);
   (void)hipGetLastError();
   delete c;
   return LGP_OK;
@@ -1044,6 +1070,79 @@ int lgp_sample_khop(lgp_ctx* c, const int32_t* seeds, int32_t n_seeds, const int
   st = sample_core(c, seeds, n_seeds, fanouts, n_hops, rng_seed, out, s);
   prof_end(c, ev, s);
   return st;
+}
+
+int lgp_sample_extract(lgp_ctx* c, const int32_t* seeds, int32_t n_seeds, const int32_t* fanouts, int32_t n_hops,
+                       uint64_t rng_seed, const lgp_sample_out* out, void* rows, int32_t* groups, int32_t* stats,
+                       void* stream) {
+  if (!c) return LGP_EINVAL;
+  if (n_seeds < 0 || (n_seeds > 0 && !seeds) || !out) return fail(c, LGP_EINVAL, "seeds / n_seeds / out");
+  int st = check_fanouts(c, fanouts, n_hops);
+  if (st != LGP_OK) return st;
+  if (!c->g.features) return fail(c, LGP_ESTATE, "the graph was created without a feature table");
+  if (!out->n_frontier || !out->n_gather) return fail(c, LGP_EINVAL, "out has null count pointers");
+  int64_t need[LGP_MAX_HOPS + 1], gather_need;
+  worst_case(c, n_seeds, fanouts, n_hops, need, &gather_need);
+  for (int h = 0; h < n_hops; ++h) {
+    if (need[h] > 0 && (!out->nbr[h] || !out->cnt[h] || (h > 0 && !out->frontier[h])))
+      return fail(c, LGP_EINVAL, "out has a null hop buffer");
+    if (out->cap[h] < need[h]) return fail(c, LGP_ECAPACITY, "out->cap[h] is below the worst-case frontier size");
+  }
+  if (out->frontier[n_hops] && out->cap[n_hops] < need[n_hops])
+    return fail(c, LGP_ECAPACITY, "out->cap[n_hops] is below the worst-case size of the last frontier");
+  // the seeds are listed as given, so a seed list with duplicates needs at least its own length
+  if (out->gather_cap < std::max<int64_t>(gather_need, n_seeds))
+    return fail(c, LGP_ECAPACITY, "out->gather_cap is below the worst case");
+  if (gather_need > 0 && (!out->gather_ids || !rows)) return fail(c, LGP_EINVAL, "out->gather_ids / rows is null");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipStream_t x = c->extract_stream;
+  LGP_HIP(c, hipSetDevice(c->di.device));
+  if (0 < c->plan.n_feat && c->plan.n_feat < c->g.num_vertices) {   // the partition lists must exist before anything is enqueued
+    st = ensure_lists(c, out->gather_cap, s);
+    if (st != LGP_OK) return st;
+  }
+  const TopoView tv = topo_view(c);
+  uint32_t* fbits32 = reinterpret_cast<uint32_t*>(c->fbits);
+  uint32_t* gbits32 = reinterpret_cast<uint32_t*>(c->gbits);
+  const int n_groups = n_hops + 1;
+  // group 0: the seeds' rows, extracted while the first hop is being sampled
+  launch_begin_listing(c->di, seeds, n_seeds, out->gather_ids, c->seg, c->seg_counters, n_groups * 3, s);
+  LGP_HIP(c, hipEventRecord(c->ev_group[0], s));
+  LGP_HIP(c, hipStreamWaitEvent(x, c->ev_group[0], 0));
+  st = gather_core(c, -1, out->gather_ids, out->gather_cap, nullptr, rows, c->seg_counters, x, nullptr, 0, c->seg,
+                   std::max<int64_t>(n_seeds, 1));
+  if (st != LGP_OK) return st;
+  const int32_t* frontier = seeds;
+  int64_t cap = n_seeds;
+  for (int h = 0; h < n_hops; ++h) {
+    launch_sample_hop(c->di, tv, frontier, out->n_frontier + h, cap, fanouts[h], h, rng_seed, out->nbr[h], out->cnt[h],
+                      fbits32, h == 0 ? gbits32 : nullptr, nullptr, c->d_err, s);
+    // next frontier (if anyone needs it as a list) and the vertices this hop reached first, appended to the listing
+    const bool want = (h + 1 < n_hops) || out->frontier[n_hops] != nullptr;
+    int32_t* next = want ? out->frontier[h + 1] : nullptr;
+    const bool last = h + 1 == n_hops;
+    launch_compact_new(c->di, c->fbits, c->gbits, c->n_chunks, c->chunk_counts, c->new_counts, next,
+                       next ? out->cap[h + 1] : 0, want ? out->n_frontier + h + 1 : nullptr, out->gather_ids,
+                       out->gather_cap, c->seg + h + 1, last ? out->n_gather : nullptr, c->d_err, s);
+    LGP_HIP(c, hipEventRecord(c->ev_group[h + 1], s));
+    LGP_HIP(c, hipStreamWaitEvent(x, c->ev_group[h + 1], 0));
+    st = gather_core(c, -1, out->gather_ids, out->gather_cap, nullptr, rows, c->seg_counters + 3 * (h + 1), x, nullptr, 0,
+                     c->seg + h + 1, std::max<int64_t>(need[h + 1], 1));
+    if (st != LGP_OK) return st;
+    frontier = next;
+    cap = next ? out->cap[h + 1] : 0;
+  }
+  // the "seen" bitmap of this batch is not compacted (the listing replaces the ascending list), so clear it whole
+  launch_fill_i32(c->di, reinterpret_cast<int32_t*>(c->gbits), c->n_chunks * kChunkWords * 2, 0, s);
+  if (stats) launch_sum_stats(c->seg_counters, n_groups, stats, x);
+  if (groups) {
+    LGP_HIP(c, hipMemcpyAsync(groups, c->seg, sizeof(int32_t) * size_t(n_hops + 2), hipMemcpyDeviceToDevice, x));
+  }
+  LGP_HIP(c, hipEventRecord(c->ev_extracted, x));
+  LGP_HIP(c, hipStreamWaitEvent(s, c->ev_extracted, 0));
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail_hip(c, e, "intra-batch pipeline launch");
+  return LGP_OK;
 }
 
 int lgp_build_blocks(lgp_ctx* c, const int32_t* seeds, int32_t n_seeds, const int32_t* fanouts, int32_t n_hops,

@@ -76,6 +76,19 @@ void launch_accumulate_sizes(const int32_t* n, int32_t count, unsigned long long
 void launch_compact(const DeviceInfo& di, uint64_t* bits, uint64_t* or_into, int64_t n_chunks, int32_t* chunk_counts,
                     int32_t* out, int64_t out_cap, int32_t* n_out, uint32_t* bump, uint32_t* d_err, hipStream_t s);
 
+// Compaction for the intra-batch pipeline: like launch_compact(bits, or_into = seen, ...), and in addition the
+// vertices marked in `bits` but not yet in `seen` -- the ones this hop reached first -- are appended, ascending,
+// to listed[seg[0] ..], and seg[1] = seg[0] + their number (seg: device int32 pair).  With n_out == nullptr no
+// frontier list is written; n_listed, if given, also receives seg[1].  new_counts: n_chunks ints of scratch.
+void launch_compact_new(const DeviceInfo& di, uint64_t* bits, uint64_t* seen, int64_t n_chunks, int32_t* chunk_counts,
+                        int32_t* new_counts, int32_t* out, int64_t out_cap, int32_t* n_out, int32_t* listed,
+                        int64_t listed_cap, int32_t* seg, int32_t* n_listed, uint32_t* d_err, hipStream_t s);
+// seg[0] = 0, seg[1] = n_seeds, listed[0 .. n_seeds) = seeds, counters[0 .. n_counters) = 0.
+void launch_begin_listing(const DeviceInfo& di, const int32_t* seeds, int64_t n_seeds, int32_t* listed, int32_t* seg,
+                          int32_t* counters, int32_t n_counters, hipStream_t s);
+// stats[0 .. 2) = column sums of the n_seg x 3 matrix seg_counters (first two columns), one thread.
+void launch_sum_stats(const int32_t* seg_counters, int32_t n_seg, int32_t* stats, hipStream_t s);
+
 // ---- gather.hip -----------------------------------------------------------
 // Look up every id in the feature remap and append (row, slot) to the hit list (list 0) or
 // (row, id) to the miss list (list 1).  With n_lists = 3, hits whose slot lies outside
@@ -87,7 +100,8 @@ struct PartLists {
 };
 void launch_partition(const DeviceInfo& di, const int32_t* ids, int64_t n_max, const int32_t* n_dev,
                       const int32_t* f_remap, int64_t num_vertices, const PartLists& out, int n_lists,
-                      int32_t local_lo, int32_t local_hi, int32_t* counters, uint32_t* d_err, hipStream_t s);
+                      int32_t local_lo, int32_t local_hi, int32_t* counters, uint32_t* d_err, hipStream_t s,
+                      const int32_t* window = nullptr, int64_t grid_items = 0);
 // "Direct" launches skip the partition: when every row is cached (or none is) the source-row
 // array is the caller's id list itself.
 struct DirectIds {
@@ -96,17 +110,21 @@ struct DirectIds {
   int32_t* stats;         // {n_hit, n_miss} to fill in, or nullptr
   int32_t stats_slot;     // which of the two gets the row count
   uint32_t* d_err;
+  const int32_t* window;  // device {begin, end}: only these entries of the array are gathered (nullptr = all)
 };
 
 // dst[row[e], :] = src[srcrow[e], :] for e < *n_dev (or n_max if n_dev is null); rows are
 // row_bytes wide; `row` and `srcrow` may each be null (= e).  streaming = source is read once over
 // PCIe (non-temporal loads, one lane group per row).
 // With ev_start and ev_stop given (and n_max > 0) the kernel's own start and stop times are recorded
-// into them.  beside_pcie: this HBM-bound gather runs at the same time as a PCIe-bound one.
+// into them.  beside_pcie: this HBM-bound gather runs at the same time as a PCIe-bound one.  With
+// dir.window given, entries [window[0], window[1]) are gathered (their output rows keep their absolute
+// numbers) and grid_items is the most entries the window can hold, for sizing the grid.
 void launch_gather_rows(const DeviceInfo& di, const void* src, void* dst, int64_t row_bytes, const int32_t* row,
                         const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, bool streaming, hipStream_t s,
-                        const DirectIds& dir = DirectIds{nullptr, 0, nullptr, 0, nullptr},
-                        hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr, bool beside_pcie = false);
+                        const DirectIds& dir = DirectIds{nullptr, 0, nullptr, 0, nullptr, nullptr},
+                        hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr, bool beside_pcie = false,
+                        int64_t grid_items = 0);
 
 // ---- blocks.hip -----------------------------------------------------------
 constexpr int kScanTile = 1024;   // elements per workgroup of the counts -> offsets scan

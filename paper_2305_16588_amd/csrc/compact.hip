@@ -97,6 +97,122 @@ __global__ __launch_bounds__(kCompactThreads) void emit_bits_kernel(
   }
 }
 
+// ---- intra-batch pipeline: frontier list + "reached first by this hop" list in one pass ---------------
+// Same two-kernel scheme with two counts per chunk: all marked vertices (the next frontier) and those
+// not yet in `seen` (the vertices whose feature rows can be extracted now).
+__global__ __launch_bounds__(kCompactThreads) void count_new_bits_kernel(const uint64_t* __restrict__ bits,
+                                                                         const uint64_t* __restrict__ seen,
+                                                                         int32_t* __restrict__ chunk_counts,
+                                                                         int32_t* __restrict__ new_counts) {
+  const int64_t word0 = int64_t(blockIdx.x) * kChunkWords + int64_t(threadIdx.x) * kWordsPerThread;
+  int c = 0, cn = 0;
+#pragma unroll
+  for (int q = 0; q < kWordsPerThread; ++q) {
+    const uint64_t x = bits[word0 + q];
+    c += __popcll(x);
+    if (x) cn += __popcll(x & ~seen[word0 + q]);
+  }
+  int total, total_new;
+  block_exclusive_scan(c, &total);
+  block_exclusive_scan(cn, &total_new);
+  if (threadIdx.x == 0) {
+    chunk_counts[blockIdx.x] = total;
+    new_counts[blockIdx.x] = total_new;
+  }
+}
+
+template <bool WITH_OUT>
+__global__ __launch_bounds__(kCompactThreads) void emit_new_bits_kernel(
+    uint64_t* __restrict__ bits, uint64_t* __restrict__ seen, const int32_t* __restrict__ chunk_counts,
+    const int32_t* __restrict__ new_counts, int32_t* __restrict__ out, int64_t out_cap, int32_t* __restrict__ n_out,
+    int32_t* __restrict__ listed, int64_t listed_cap, int32_t* __restrict__ seg, int32_t* __restrict__ n_listed,
+    uint32_t* __restrict__ d_err, int shift) {
+  const int64_t word0 = int64_t(blockIdx.x) * kChunkWords + int64_t(threadIdx.x) * kWordsPerThread;
+  uint64_t w[kWordsPerThread], fresh[kWordsPerThread];
+  int c = 0, cn = 0;
+#pragma unroll
+  for (int q = 0; q < kWordsPerThread; ++q) {
+    w[q] = bits[word0 + q];
+    fresh[q] = w[q] ? (w[q] & ~seen[word0 + q]) : 0ull;
+    c += __popcll(w[q]);
+    cn += __popcll(fresh[q]);
+  }
+  int part = 0, part_new = 0;
+  for (int k = threadIdx.x; k < int(blockIdx.x); k += kCompactThreads) {
+    part += chunk_counts[k];
+    part_new += new_counts[k];
+  }
+  int before, before_new, mine, mine_new;
+  block_exclusive_scan(part, &before);
+  block_exclusive_scan(part_new, &before_new);
+  const int excl = block_exclusive_scan(c, &mine);
+  const int excl_new = block_exclusive_scan(cn, &mine_new);
+  const int64_t base = seg[0];
+  int64_t pos = int64_t(before) + excl;
+  int64_t pos_new = base + before_new + excl_new;
+  if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+    const int64_t total = int64_t(before) + mine;
+    if (WITH_OUT) {
+      *n_out = int32_t(total <= out_cap ? total : out_cap);
+      if (total > out_cap) atomicOr(d_err, ERR_OVERRUN);
+    }
+    int64_t end = base + before_new + mine_new;
+    if (end > listed_cap) {
+      atomicOr(d_err, ERR_OVERRUN);
+      end = listed_cap;
+    }
+    seg[1] = int32_t(end);
+    if (n_listed) *n_listed = int32_t(end);
+  }
+  if (c == 0) return;
+#pragma unroll
+  for (int q = 0; q < kWordsPerThread; ++q) {
+    uint64_t x = w[q];
+    if (x == 0) continue;
+    if (fresh[q]) seen[word0 + q] |= x;
+    bits[word0 + q] = 0;
+    const int64_t id0 = (word0 + q) * 64;
+    const uint64_t f = fresh[q];
+    while (x) {
+      const int b = __ffsll((unsigned long long)x) - 1;
+      const int32_t id = int32_t((id0 + b) >> shift);
+      if (WITH_OUT) {
+        if (pos < out_cap) out[pos] = id;
+        ++pos;
+      }
+      if ((f >> b) & 1ull) {
+        if (pos_new < listed_cap) listed[pos_new] = id;
+        ++pos_new;
+      }
+      x &= x - 1;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void begin_listing_kernel(const int32_t* __restrict__ seeds, int64_t n_seeds,
+                                                            int32_t* __restrict__ listed, int32_t* __restrict__ seg,
+                                                            int32_t* __restrict__ counters, int32_t n_counters) {
+  const int64_t t = int64_t(blockIdx.x) * 256 + threadIdx.x;
+  if (t == 0) {
+    seg[0] = 0;
+    seg[1] = int32_t(n_seeds);
+  }
+  if (t < n_counters) counters[t] = 0;
+  for (int64_t i = t; i < n_seeds; i += int64_t(gridDim.x) * 256) listed[i] = seeds[i];
+}
+
+__global__ void sum_stats_kernel(const int32_t* __restrict__ seg_counters, int32_t n_seg, int32_t* __restrict__ stats) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    int32_t hit = 0, miss = 0;
+    for (int32_t k = 0; k < n_seg; ++k) {
+      hit += seg_counters[3 * k];
+      miss += seg_counters[3 * k + 1];
+    }
+    stats[0] = hit;
+    stats[1] = miss;
+  }
+}
+
 }  // namespace
 
 void launch_compact(const DeviceInfo& di, uint64_t* bits, uint64_t* or_into, int64_t n_chunks, int32_t* chunk_counts,
@@ -109,6 +225,34 @@ void launch_compact(const DeviceInfo& di, uint64_t* bits, uint64_t* or_into, int
     hipLaunchKernelGGL((emit_bits_kernel<false>), dim3(unsigned(n_chunks)), dim3(kCompactThreads), 0, s, bits,
                        or_into, chunk_counts, out, out_cap, n_out, bump, d_err, di.spread_shift);
   }
+}
+
+void launch_compact_new(const DeviceInfo& di, uint64_t* bits, uint64_t* seen, int64_t n_chunks, int32_t* chunk_counts,
+                        int32_t* new_counts, int32_t* out, int64_t out_cap, int32_t* n_out, int32_t* listed,
+                        int64_t listed_cap, int32_t* seg, int32_t* n_listed, uint32_t* d_err, hipStream_t s) {
+  hipLaunchKernelGGL(count_new_bits_kernel, dim3(unsigned(n_chunks)), dim3(kCompactThreads), 0, s, bits, seen,
+                     chunk_counts, new_counts);
+  if (n_out)
+    hipLaunchKernelGGL((emit_new_bits_kernel<true>), dim3(unsigned(n_chunks)), dim3(kCompactThreads), 0, s, bits, seen,
+                       chunk_counts, new_counts, out, out_cap, n_out, listed, listed_cap, seg, n_listed, d_err,
+                       di.spread_shift);
+  else
+    hipLaunchKernelGGL((emit_new_bits_kernel<false>), dim3(unsigned(n_chunks)), dim3(kCompactThreads), 0, s, bits, seen,
+                       chunk_counts, new_counts, out, out_cap, n_out, listed, listed_cap, seg, n_listed, d_err,
+                       di.spread_shift);
+}
+
+void launch_begin_listing(const DeviceInfo& di, const int32_t* seeds, int64_t n_seeds, int32_t* listed, int32_t* seg,
+                          int32_t* counters, int32_t n_counters, hipStream_t s) {
+  int64_t blocks = (n_seeds + 255) / 256;
+  if (blocks > di.num_cus * 4) blocks = di.num_cus * 4;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(begin_listing_kernel, dim3(unsigned(blocks)), dim3(256), 0, s, seeds, n_seeds, listed, seg,
+                     counters, n_counters);
+}
+
+void launch_sum_stats(const int32_t* seg_counters, int32_t n_seg, int32_t* stats, hipStream_t s) {
+  hipLaunchKernelGGL(sum_stats_kernel, dim3(1), dim3(64), 0, s, seg_counters, n_seg, stats);
 }
 
 }  // namespace lgp

@@ -38,14 +38,19 @@ template <int NL>
 __global__ __launch_bounds__(256) void partition_kernel(
     const int32_t* __restrict__ ids, int64_t n_max, const int32_t* __restrict__ n_dev,
     const int32_t* __restrict__ f_remap, int64_t num_vertices, PartLists out, int32_t local_lo, int32_t local_hi,
-    int32_t* __restrict__ counters, uint32_t* __restrict__ d_err) {
+    int32_t* __restrict__ counters, uint32_t* __restrict__ d_err, const int32_t* __restrict__ window) {
   __shared__ int wave_cnt[NL][4], block_base[NL];
   int64_t n = n_dev ? int64_t(*n_dev) : n_max;
+  int64_t lo = 0;
+  if (window) {                                     // entries [window[0], window[1]) of ids
+    lo = window[0] < 0 ? 0 : window[0];
+    n = window[1];
+  }
   if (n > n_max) n = n_max;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint64_t lower = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
   constexpr int kTile = 256 * kPartItems;
-  for (int64_t base = int64_t(blockIdx.x) * kTile; base < n; base += int64_t(gridDim.x) * kTile) {
+  for (int64_t base = lo + int64_t(blockIdx.x) * kTile; base < n; base += int64_t(gridDim.x) * kTile) {
     int32_t src[kPartItems];
     uint64_t mask[NL][kPartItems];
     int cnt[NL];
@@ -105,7 +110,7 @@ __global__ __launch_bounds__(256) void partition_kernel(
 
 __device__ __forceinline__ void direct_stats(const DirectIds& dir, int64_t n) {
   if (dir.stats && blockIdx.x == 0 && threadIdx.x == 0) {
-    dir.stats[dir.stats_slot] = int32_t(n);
+    dir.stats[dir.stats_slot] = int32_t(n > 0 ? n : 0);
     dir.stats[1 - dir.stats_slot] = 0;
   }
 }
@@ -133,14 +138,19 @@ __global__ __launch_bounds__(256) void gather_rows_flat_kernel(const VecT* __res
                                                                const int32_t* __restrict__ n_dev, DirectIds dir,
                                                                int epw) {
   int64_t n = n_dev ? int64_t(*n_dev) : n_max;
+  int64_t lo = 0;
+  if (dir.window) {                                 // entries [window[0], window[1]) only
+    lo = dir.window[0] < 0 ? 0 : dir.window[0];
+    n = dir.window[1];
+  }
   if (n > n_max) n = n_max;
-  direct_stats(dir, n);
+  direct_stats(dir, n - lo);
   const int lane = threadIdx.x & 63;
   const int64_t wave = (int64_t(blockIdx.x) * 256 + threadIdx.x) >> 6;
   const int64_t n_waves = int64_t(gridDim.x) * 4;
   // epw (<= 64) list entries per wave and pass: fewer for wide rows, so that a pass moves a few tens of
   // KiB and the passes spread evenly over the waves whatever the (device-side) number of entries is
-  for (int64_t e0 = wave * epw; e0 < n; e0 += n_waves * epw) {
+  for (int64_t e0 = lo + wave * epw; e0 < n; e0 += n_waves * epw) {
     const int64_t e = e0 + lane;
     const bool mine = lane < epw && e < n;
     const int32_t my_row = mine ? (row ? row[e] : int32_t(e)) : 0;
@@ -184,15 +194,20 @@ __global__ __launch_bounds__(256) void gather_rows_group_kernel(const VecT* __re
                                                                 const int32_t* __restrict__ srcrow, int64_t n_max,
                                                                 const int32_t* __restrict__ n_dev, DirectIds dir) {
   int64_t n = n_dev ? int64_t(*n_dev) : n_max;
+  int64_t lo = 0;
+  if (dir.window) {
+    lo = dir.window[0] < 0 ? 0 : dir.window[0];
+    n = dir.window[1];
+  }
   if (n > n_max) n = n_max;
-  direct_stats(dir, n);
+  direct_stats(dir, n - lo);
   const uint32_t sub = threadIdx.x % G;
   const int64_t group = (int64_t(blockIdx.x) * 256 + threadIdx.x) / G;
   const int64_t n_groups = int64_t(gridDim.x) * (256 / G);
   // The list entries of the next pass are loaded before the rows of this one, so that a pass waits
   // for one round trip to memory (its rows), not two in a row (entries, then rows).
   int32_t next_src[UNROLL], next_row[UNROLL];
-  const int64_t first = group * UNROLL;
+  const int64_t first = lo + group * UNROLL;
 #pragma unroll
   for (int u = 0; u < UNROLL; ++u) {
     const int64_t e = first + u;
@@ -239,6 +254,7 @@ struct Where {
   hipStream_t s;
   hipEvent_t a, b;
   int64_t hbm_blocks;   // most workgroups an HBM-bound gather may use
+  int64_t items;        // entries to size the grid for (<= n_max: a window covers part of the array)
 };
 
 template <typename K, typename... Args>
@@ -262,7 +278,7 @@ void launch_flat(const DeviceInfo& di, const void* src, void* dst, int64_t row_b
   // waves with one pass and a few with two (216.6 -> 195.7 us; 379 k such rows: 311.5 -> 263.8 us).
   int epw = 64;
   while (epw > 4 && int64_t(epw) * row_bytes > 32768) epw >>= 1;
-  const unsigned blocks = blocks_for((n_max + 4 * epw - 1) / (4 * epw), std::min<int64_t>(s.hbm_blocks, int64_t(di.num_cus) * 3));
+  const unsigned blocks = blocks_for((s.items + 4 * epw - 1) / (4 * epw), std::min<int64_t>(s.hbm_blocks, int64_t(di.num_cus) * 3));
   // Rows made of whole 128-byte lines are read once: stream them past L2 (+2.5 % at 512-B and 2-KiB
   // rows).  Rows that straddle lines share their boundary lines between consecutive load
   // instructions, and L2 has to merge those (non-temporal loads cost 7 % on 400-B rows).
@@ -282,7 +298,7 @@ void launch_group_g(const DeviceInfo& di, const void* src, void* dst, uint32_t c
   // workgroup per four CUs holds ~1 MB of reads in flight, and measured rates FALL with wider grids
   // (400-B rows 44.9 -> 44.0 GB/s, 2-KiB rows 57.5 -> 55.7 GB/s from 64 to 512 workgroups), because the
   // excess requests only queue up in front of the link.
-  const unsigned blocks = blocks_for((n_max + (256 / G) * U - 1) / ((256 / G) * U), std::max(1, di.num_cus / 4));
+  const unsigned blocks = blocks_for((s.items + (256 / G) * U - 1) / ((256 / G) * U), std::max(1, di.num_cus / 4));
   launch_on(s, gather_rows_group_kernel<VecT, G, U, false>, blocks,
                      static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, row, srcrow, n_max, n_dev, dir);
 }
@@ -296,7 +312,7 @@ void launch_group_hbm_g(const DeviceInfo& di, const void* src, void* dst, uint32
                         const Where& s) {
   // one row per group in flight needs more waves than the flat walk: 6 workgroups per CU (400-byte rows,
   // 512 k hits: 138.7 / 107.6 / 95.6 / 90.7 / 91.4 us at 2 / 3 / 4 / 6 / 8 workgroups per CU)
-  const unsigned blocks = blocks_for((n_max + 256 / G - 1) / (256 / G), std::min<int64_t>(s.hbm_blocks, int64_t(di.num_cus) * 6));
+  const unsigned blocks = blocks_for((s.items + 256 / G - 1) / (256 / G), std::min<int64_t>(s.hbm_blocks, int64_t(di.num_cus) * 6));
   launch_on(s, gather_rows_group_kernel<VecT, G, 1, true>, blocks,
                      static_cast<const VecT*>(src), static_cast<VecT*>(dst), cpr, row, srcrow, n_max, n_dev, dir);
 }
@@ -325,31 +341,35 @@ void launch_group(const DeviceInfo& di, const void* src, void* dst, int64_t row_
 
 void launch_partition(const DeviceInfo& di, const int32_t* ids, int64_t n_max, const int32_t* n_dev,
                       const int32_t* f_remap, int64_t num_vertices, const PartLists& out, int n_lists,
-                      int32_t local_lo, int32_t local_hi, int32_t* counters, uint32_t* d_err, hipStream_t s) {
+                      int32_t local_lo, int32_t local_hi, int32_t* counters, uint32_t* d_err, hipStream_t s,
+                      const int32_t* window, int64_t grid_items) {
   const bool three = n_lists == 3;
   hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(64), 0, s, counters, three ? 3 : 2);
-  int64_t blocks = (n_max + 256 * kPartItems - 1) / (256 * kPartItems);
+  const int64_t items = (window && grid_items > 0 && grid_items < n_max) ? grid_items : n_max;
+  int64_t blocks = (items + 256 * kPartItems - 1) / (256 * kPartItems);
   const int64_t full = int64_t(di.num_cus) * 8;
   if (blocks > full) blocks = full;
   if (blocks < 1) blocks = 1;
   if (three)
     hipLaunchKernelGGL(partition_kernel<3>, dim3(unsigned(blocks)), dim3(256), 0, s, ids, n_max, n_dev, f_remap,
-                       num_vertices, out, local_lo, local_hi, counters, d_err);
+                       num_vertices, out, local_lo, local_hi, counters, d_err, window);
   else
     hipLaunchKernelGGL(partition_kernel<2>, dim3(unsigned(blocks)), dim3(256), 0, s, ids, n_max, n_dev, f_remap,
-                       num_vertices, out, 0, 0, counters, d_err);
+                       num_vertices, out, 0, 0, counters, d_err, window);
 }
 
 void launch_gather_rows(const DeviceInfo& di, const void* src, void* dst, int64_t row_bytes, const int32_t* row,
                         const int32_t* srcrow, int64_t n_max, const int32_t* n_dev, bool streaming, hipStream_t stream,
-                        const DirectIds& dir, hipEvent_t ev_start, hipEvent_t ev_stop, bool beside_pcie) {
+                        const DirectIds& dir, hipEvent_t ev_start, hipEvent_t ev_stop, bool beside_pcie,
+                        int64_t grid_items) {
   if (n_max <= 0) return;
   // An HBM-bound gather is capped at 8 workgroups per CU (each kernel narrows that further).  One that runs beside a
   // PCIe-bound kernel is throttled by the PCIe reads queued ahead of it whatever its width, and
   // in turn delays them; two workgroups per CU keep it out of the link's way (measured on 400-byte
   // rows, 506 k hits beside 253 k misses: the miss gather takes 2.40 ms beside a full-width hit
   // gather, 2.24 ms beside a narrow one, and the step 2.49 ms instead of 2.66 ms).
-  const Where s{stream, ev_start, ev_stop, int64_t(di.num_cus) * (beside_pcie ? 2 : 8)};
+  const Where s{stream, ev_start, ev_stop, int64_t(di.num_cus) * (beside_pcie ? 2 : 8),
+                (grid_items > 0 && grid_items < n_max) ? grid_items : n_max};
   const uintptr_t align = uintptr_t(src) | uintptr_t(dst) | uintptr_t(row_bytes);
 #define LGP_ROWS(VecT)                                                                        \
   do {                                                                                        \
