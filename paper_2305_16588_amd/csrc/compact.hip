@@ -38,6 +38,23 @@ __device__ __forceinline__ int block_exclusive_scan(int x, int* total) {
   return before + inc - x;
 }
 
+// This thread's share of counts[0 .. n): eight loads in flight per round, so that a workgroup far down the
+// bitmap (thousands of chunks before it) waits for one or two round trips to L2, not for one per 256 chunks.
+__device__ __forceinline__ int sum_before(const int32_t* __restrict__ counts, int n) {
+  int part = 0;
+  for (int k0 = 0; k0 < n; k0 += kCompactThreads * 8) {
+    int v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int k = k0 + j * kCompactThreads + int(threadIdx.x);
+      v[j] = k < n ? counts[k] : 0;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) part += v[j];
+  }
+  return part;
+}
+
 __global__ __launch_bounds__(kCompactThreads) void count_bits_kernel(const uint64_t* __restrict__ bits,
                                                                      int32_t* __restrict__ chunk_counts) {
   const uint64_t* w = bits + int64_t(blockIdx.x) * kChunkWords + int64_t(threadIdx.x) * kWordsPerThread;
@@ -64,8 +81,7 @@ __global__ __launch_bounds__(kCompactThreads) void emit_bits_kernel(
   }
   int64_t pos = 0;
   if (WITH_OUT) {
-    int part = 0;
-    for (int k = threadIdx.x; k < int(blockIdx.x); k += kCompactThreads) part += chunk_counts[k];
+    const int part = sum_before(chunk_counts, int(blockIdx.x));
     int before_chunks, mine_total;
     block_exclusive_scan(part, &before_chunks);
     const int excl = block_exclusive_scan(c, &mine_total);
@@ -137,11 +153,8 @@ __global__ __launch_bounds__(kCompactThreads) void emit_new_bits_kernel(
     c += __popcll(w[q]);
     cn += __popcll(fresh[q]);
   }
-  int part = 0, part_new = 0;
-  for (int k = threadIdx.x; k < int(blockIdx.x); k += kCompactThreads) {
-    part += chunk_counts[k];
-    part_new += new_counts[k];
-  }
+  const int part = sum_before(chunk_counts, int(blockIdx.x));
+  const int part_new = sum_before(new_counts, int(blockIdx.x));
   int before, before_new, mine, mine_new;
   block_exclusive_scan(part, &before);
   block_exclusive_scan(part_new, &before_new);
