@@ -3,15 +3,17 @@
 
 One step = sample_khop + gather_features for one mini-batch of the workload's
 training tablet (all per-batch stages; the caches are built beforehand from a
-pre-sampling epoch, whose time is reported separately).  Inputs are seeded and
+pre-sampling epoch, whose time is reported separately; the timed steps use other
+rng seeds than that epoch, so cache hit rates are those of a later epoch).  Inputs are seeded and
 synthetic (see datagen) and are resident -- graph and feature table in pinned CPU
 memory (or HBM where the table exceeds what a process may pin), caches in HBM --
 before the timed region starts.
 
 The headline is the largest single-GPU workload ("share": one GPU's share of a
-billion-scale graph).  The timed region is run R times (--reps), K steps each;
-`value` / `ms_per_step` are the mean over all R x K steps, the median of the R
-regions is reported beside it.  `configs` holds one shorter record per other
+billion-scale graph).  The timed region of K steps is run R times (--reps; by
+default as often as it takes to time at least half a second of work, and at
+least five times); `value` / `ms_per_step` are the mean over all R x K steps,
+the median, minimum and maximum of the R regions are reported beside it.  `configs` holds one shorter record per other
 workload (tiny, mid, large, and the wide-feature sweep over the feature-cache
 ratio), each with its own rooflines.
 
@@ -113,6 +115,12 @@ class Inputs:
         torch.cuda.empty_cache()
 
 
+def step_seed(spec, i: int) -> int:
+    """rng seed of timed step i.  Pre-sampling used base_seed + b for batch b, so the timed steps draw other
+    samples than the ones the caches were ranked on -- as later epochs of a training job do."""
+    return spec.base_seed + (1 << 20) + i
+
+
 def timed_regions(fn, first: int, steps: int, reps: int):
     """R back-to-back timed regions of K calls fn(i), each bracketed by a device synchronisation."""
     import torch
@@ -165,13 +173,13 @@ def measure(inp: Inputs, steps: int, warmup: int, reps: int, topo_frac=None, fea
     t_cache = time.time() - t0
 
     L = len(spec.fanouts)
-    total = warmup + reps * steps
+    total = warmup + max(reps, 5) * steps
     buf = lgp.SampleBuffers(V, spec.batch, spec.fanouts)
     rows = torch.empty((buf.gather_cap, D), dtype=ctx.feat_torch_dtype, device="cuda")
     stats = torch.zeros((total, 2), dtype=torch.int32, device="cuda")
 
     def step(i: int):
-        ctx.sample_khop(inp.seeds(i), spec.fanouts, spec.base_seed + i, out=buf)
+        ctx.sample_khop(inp.seeds(i), spec.fanouts, step_seed(spec, i), out=buf)
         ctx.gather_features(buf.gather_ids, n_dev=buf.n_gather, out=rows, stats=stats[i])
 
     for i in range(warmup):
@@ -188,6 +196,15 @@ def measure(inp: Inputs, steps: int, warmup: int, reps: int, topo_frac=None, fea
     # `roofline_pcie`), which those launches record themselves.  The full breakdown of `per_step` and the sampler's
     # work counts come from an untimed pass over the first region's K steps with events around every kernel group.
     ctx.set_profiling(2)
+    if reps <= 0:                                       # auto: at least 0.5 s of timed work, at least 5 regions
+        probe = timed_regions(step, warmup, steps, 1)[0]
+        reps = max(5, min(400, int(0.5 / max(probe, 1e-6)) + 1))
+        ctx.get_profile()                               # the probe region's events are not part of the figures
+        if warmup + reps * steps > stats.shape[0]:
+            stats = torch.zeros((warmup + reps * steps, 2), dtype=torch.int32, device="cuda")
+            for i in range(warmup):                     # `step` writes into the new tensor from here on
+                step(i)
+            torch.cuda.synchronize()
     regions = timed_regions(step, warmup, steps, reps)
     prof_g = ctx.get_profile()
     ctx.check()
@@ -271,7 +288,8 @@ def measure(inp: Inputs, steps: int, warmup: int, reps: int, topo_frac=None, fea
         "value": round(n_steps * spec.batch / elapsed, 1), "unit": "seeds/s", "steps": steps, "warmup": warmup,
         "reps": reps, "ms_per_step": round(ms_per_step, 4),
         "ms_per_step_median": round(statistics.median(per_region), 4),
-        "ms_per_step_regions": [round(t, 4) for t in per_region],
+        "ms_per_step_min": round(min(per_region), 4), "ms_per_step_max": round(max(per_region), 4),
+        "timed_s": round(elapsed, 4),
         "config": {"workload": f"{inp.spec.name}: V={V} E={E} D={D} {spec.feat_dtype} fanouts={list(spec.fanouts)} "
                                f"batch={spec.batch} topo_cache={spec.topo_frac:g} feat_cache={spec.feat_frac:g}"
                                + (" (source feature table in HBM: the box pins at most 64 GiB of host memory)"
@@ -295,7 +313,7 @@ def measure(inp: Inputs, steps: int, warmup: int, reps: int, topo_frac=None, fea
         istats = torch.zeros((warmup + steps, 2), dtype=torch.int32, device="cuda")
 
         def istep(i: int):
-            ctx.sample_extract(inp.seeds(i), spec.fanouts, spec.base_seed + i, buf, rows, groups, istats[i])
+            ctx.sample_extract(inp.seeds(i), spec.fanouts, step_seed(spec, i), buf, rows, groups, istats[i])
 
         for i in range(warmup):
             istep(i)
@@ -355,7 +373,7 @@ def secondary_figures(inp, spec, plan, buf, rows, stats, steps, warmup, ms_per_s
         k = i % 2
         if i >= 2:
             sA.wait_event(ev_gathered[k])              # buffer k is free again
-        ctx.sample_khop(inp.seeds(i), spec.fanouts, spec.base_seed + i, out=bufs[k], stream=sA)
+        ctx.sample_khop(inp.seeds(i), spec.fanouts, step_seed(spec, i), out=bufs[k], stream=sA)
         ev_sampled[k].record(sA)
         sB.wait_event(ev_sampled[k])
         ctx.gather_features(bufs[k].gather_ids, n_dev=bufs[k].n_gather, out=outs[k], stats=pstats[i], stream=sB)
@@ -381,7 +399,7 @@ def secondary_figures(inp, spec, plan, buf, rows, stats, steps, warmup, ms_per_s
 
     def serial_step(i: int):
         seeds = inp.seeds(i)
-        ctx.sample_khop(seeds, spec.fanouts, spec.base_seed + i, out=bufs[0])
+        ctx.sample_khop(seeds, spec.fanouts, step_seed(spec, i), out=bufs[0])
         ctx.build_blocks(seeds, spec.fanouts, bufs[0], out=blks[0])
         ctx.gather_features(bufs[0].gather_ids, n_dev=bufs[0].n_gather, out=outs[0], stats=sstats[i])
 
@@ -391,7 +409,7 @@ def secondary_figures(inp, spec, plan, buf, rows, stats, steps, warmup, ms_per_s
         if i >= 2:
             sA.wait_event(ev_g[k])                      # buffer k is free again
             sA.wait_event(ev_b[k])
-        ctx.sample_khop(seeds, spec.fanouts, spec.base_seed + i, out=bufs[k], stream=sA)
+        ctx.sample_khop(seeds, spec.fanouts, step_seed(spec, i), out=bufs[k], stream=sA)
         ev_s[k].record(sA)
         sB.wait_event(ev_s[k])
         sC.wait_event(ev_s[k])
@@ -416,7 +434,7 @@ def secondary_figures(inp, spec, plan, buf, rows, stats, steps, warmup, ms_per_s
     total_ms, n_timed = 0.0, min(steps, 20)
     for i in range(warmup, warmup + n_timed + 2):
         seeds = inp.seeds(i)
-        ctx.sample_khop(seeds, spec.fanouts, spec.base_seed + i, out=bufs[0])
+        ctx.sample_khop(seeds, spec.fanouts, step_seed(spec, i), out=bufs[0])
         e0.record()
         ctx.build_blocks(seeds, spec.fanouts, bufs[0], out=blks[0])
         e1.record()
@@ -433,7 +451,7 @@ def secondary_figures(inp, spec, plan, buf, rows, stats, steps, warmup, ms_per_s
     g = torch.cuda.CUDAGraph()
     torch.cuda.synchronize()
     with torch.cuda.graph(g):
-        ctx.sample_khop(seeds_buf, spec.fanouts, spec.base_seed, out=buf)
+        ctx.sample_khop(seeds_buf, spec.fanouts, step_seed(spec, 0), out=buf)
         ctx.gather_features(buf.gather_ids, n_dev=buf.n_gather, out=rows, stats=stats[0])
 
     def replay(i: int):
@@ -486,7 +504,7 @@ def clique_figure(inp, spec, buf, rows, steps, warmup, K, topo_b, feat_b, cache_
     def cstep(i: int):
         b = i % my_batches
         seeds = tabs[0][b * spec.batch:(b + 1) * spec.batch]
-        ctx.sample_khop(seeds, spec.fanouts, spec.base_seed + i, out=buf)
+        ctx.sample_khop(seeds, spec.fanouts, step_seed(spec, i), out=buf)
         ctx.gather_features_clique(0, buf.gather_ids, n_dev=buf.n_gather, out=rows, stats=cstats[i])
 
     for i in range(warmup):
@@ -513,7 +531,7 @@ def cpu_baseline(inp: Inputs, first: int, max_batches: int, budget_s: float = 15
 
     def one(i: int):
         b = i % inp.full_batches
-        res = orc.sample_khop(inp.tablet[b * spec.batch:(b + 1) * spec.batch], spec.fanouts, spec.base_seed + i)
+        res = orc.sample_khop(inp.tablet[b * spec.batch:(b + 1) * spec.batch], spec.fanouts, step_seed(spec, i))
         orc.gather(res.gather_ids)
 
     t_cpu, done = 0.0, 0
@@ -551,7 +569,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--reps", type=int, default=5, help="timed regions of --steps steps each (mean and median reported)")
+    ap.add_argument("--reps", type=int, default=0,
+                    help="timed regions of --steps steps each (mean, median, min and max reported); 0 = as many as it "
+                         "takes to time at least 0.5 s of work, at least 5")
     ap.add_argument("--workload", default="share",
                     help="headline workload: tiny | mid | wide | large | share (optionally name@scale); the default "
                          "is the largest single-GPU one")
@@ -648,8 +668,9 @@ def main() -> int:
     line = {
         "metric": "seeds/sec through sample+gather; feature-gather GB/s vs HBM & PCIe peak",
         "value": head["value"], "unit": "seeds/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "reps": args.reps, "ms_per_step": head["ms_per_step"], "ms_per_step_median": head["ms_per_step_median"],
-        "ms_per_step_regions": head["ms_per_step_regions"],
+        "reps": head["reps"], "ms_per_step": head["ms_per_step"], "ms_per_step_median": head["ms_per_step_median"],
+        "ms_per_step_min": head["ms_per_step_min"], "ms_per_step_max": head["ms_per_step_max"],
+        "timed_s": head["timed_s"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32 ids / opaque feature bytes", "data": "synthetic",
         "config": dict(head["config"], headline_choice=fallback or (
