@@ -44,14 +44,15 @@ def source_hash() -> str:
 
 
 def is_stale() -> bool:
-    """True if a built library exists but was not built from the sources as they are now."""
+    """True if a built library exists and its stamp says it was built from other sources than the ones
+    here now.  A library without a stamp (copied in from elsewhere) is taken as it is."""
     if not os.path.exists(LIB):
         return False
     try:
         with open(STAMP) as f:
             return f.read().strip() != source_hash()
     except OSError:
-        return True
+        return False
 
 
 def build(verbose: bool = False) -> str:

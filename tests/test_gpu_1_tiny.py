@@ -531,7 +531,8 @@ def test_row_wider_than_the_limit_is_refused():
 @pytest.mark.parametrize("case", range(int(os.environ.get("LGP_RANDOM_CASES", "24"))))
 def test_randomized_small_workloads(case):
     """Random small graphs, feature widths, fan-out lists, seed sets and cache splits: sampling, blocks and
-    gathered bytes against the oracle; then the same graph with the cache of a random clique.
+    gathered bytes against the oracle, also through the fixed-scratch extraction, a random slice of the cache
+    and the intra-batch pipeline; then the same graph with the cache of a random clique.
     LGP_RANDOM_CASES sets the number of cases (default 24)."""
     import oracle
     import paper_2305_16588_amd as lgp
@@ -577,6 +578,30 @@ def test_randomized_small_workloads(case):
     assert rows[:n].cpu().numpy().tobytes() == orc.gather(ref.gather_ids).tobytes()
     n_hit = orc.count_hits(ref.gather_ids, qf, plan.n_feat)
     assert stats.tolist() == [n_hit, n - n_hit]
+    # the same extraction through the fixed scratch block, a slice of the cache, and the intra-batch pipeline
+    rows2 = torch.empty_like(rows)
+    stats.fill_(-1)
+    ctx.gather_features_static(buf.gather_ids, buf.n_gather, rows2, stats)
+    assert rows2[:n].cpu().numpy().tobytes() == orc.gather(ref.gather_ids).tobytes() and stats.tolist() == [n_hit, n - n_hit]
+    if plan.n_feat:
+        lo = int(rng.integers(0, plan.n_feat))
+        cnt = int(rng.integers(0, plan.n_feat - lo + 1))
+        assert ctx.get_cache_part(1, lo, cnt).tobytes() == orc.fill_feat(qf[lo:lo + cnt], cnt).tobytes()
+    if plan.topo_edges:
+        full = orc.fill_topo(qt, plan.n_topo)[1]
+        lo = int(rng.integers(0, plan.topo_edges))
+        cnt = int(rng.integers(0, plan.topo_edges - lo + 1))
+        assert (ctx.get_cache_part(0, lo, cnt) == full[lo:lo + cnt]).all()
+    pbuf = lgp.SampleBuffers(V, batch, fanouts)
+    prow = torch.empty((max(pbuf.gather_cap, 1), dim), dtype=ctx.feat_torch_dtype, device="cuda")
+    groups = torch.zeros(len(fanouts) + 2, dtype=torch.int32, device="cuda")
+    stats.fill_(-1)
+    ctx.sample_extract(dev, fanouts, seed, pbuf, prow, groups, stats)
+    fr, nbr, cnt_, listing = pbuf.to_host(dev)
+    for h in range(len(fanouts)):
+        assert (fr[h] == ref.frontier[h]).all() and (nbr[h] == ref.nbr[h]).all() and (cnt_[h] == ref.cnt[h]).all()
+    assert listing.tolist() == ref.hop_order.tolist() and groups.tolist() == ref.hop_seg.tolist()
+    assert prow[:n].cpu().numpy().tobytes() == orc.gather(ref.hop_order).tobytes() and stats.tolist() == [n_hit, n - n_hit]
     # the cache of a clique of k_g members with random hotness rows (many ties and zeros), three-way extraction
     k_g = int(rng.integers(1, 9))
     HT = rng.integers(0, 4, size=(k_g, V)).astype(np.uint32)
