@@ -323,7 +323,10 @@ int lgp_gather_features_static(lgp_ctx* ctx, const int32_t* ids, int64_t n_max, 
  * dominating (2.4 M vertices, 400-byte rows, 30 % of them cached): 2.49 ms per step instead
  * of 2.56 ms.  The hit gather itself takes many times longer that way (PCIe reads queued
  * ahead of it throttle it), so per-kernel timings are only meaningful with overlap off,
- * which is the default. */
+ * which is the default.  A process has a few hardware queues (four by default) and HIP
+ * spreads streams over them: if the library's stream and `stream` happen to share one, the
+ * result is the same but the two gathers run one after the other.  The same holds for
+ * lgp_sample_extract's stream. */
 int lgp_set_overlap(lgp_ctx* ctx, int enable);
 
 /* HBM the library holds or will allocate on its own for calls of one shape, in bytes, so that a
