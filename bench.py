@@ -333,43 +333,6 @@ def measure(inp: Inputs, steps: int, warmup: int, reps: int, topo_frac=None, fea
     return rec
 
 
-def concurrent_streams(n: int):
-    """n torch streams whose work runs side by side.  A process owns a handful of hardware queues, two streams that
-    land on the same one serialise, and the API does not say which do: so candidates are tried pairwise with a
-    spin kernel per stream (two spins take the time of one only when the streams are concurrent)."""
-    import torch
-
-    cur = torch.cuda.current_stream()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    spin = 2_000_000      # about a millisecond
-
-    def both(a, b) -> float:
-        torch.cuda.synchronize()
-        e0.record()
-        for st in (a, b):
-            st.wait_stream(cur)
-            with torch.cuda.stream(st):
-                torch.cuda._sleep(spin)
-        cur.wait_stream(a)
-        cur.wait_stream(b)
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1)
-
-    candidates = [torch.cuda.Stream() for _ in range(12)]
-    both(candidates[0], candidates[0])
-    alone = min(both(c, c) for c in candidates[:2]) / 2
-    chosen = [candidates[0]]
-    for c in candidates[1:]:
-        if len(chosen) == n:
-            break
-        if all(both(c, k) < 1.5 * alone for k in chosen):
-            chosen.append(c)
-    concurrent = len(chosen) == n
-    chosen += [c for c in candidates if c not in chosen][:n - len(chosen)]
-    return chosen, concurrent
-
-
 def secondary_figures(inp, spec, plan, buf, rows, stats, steps, warmup, ms_per_step, overlap, step):
     """The pipelines of Sec. 5 and a HIP-graph replay over the same K steps (never the headline)."""
     import torch
@@ -399,7 +362,7 @@ def secondary_figures(inp, spec, plan, buf, rows, stats, steps, warmup, ms_per_s
 
     # inter-batch pipeline: sampling of batch i+1 on a second stream beside the feature extraction of batch i
     ctx.set_overlap(overlap or both_gathers)
-    (sA, sB, sC), streams_concurrent = concurrent_streams(3)
+    (sA, sB, sC), streams_concurrent = lgp.concurrent_streams(3)
     bufs = [buf, lgp.SampleBuffers(V, spec.batch, spec.fanouts)]
     outs = [rows, torch.empty_like(rows)]
     ev_sampled = [torch.cuda.Event(), torch.cuda.Event()]

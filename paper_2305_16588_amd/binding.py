@@ -497,3 +497,40 @@ class Context:
         p = Profile()
         self._ok(self._L.lgp_get_profile(self._h, C.byref(p)))
         return p
+
+
+def concurrent_streams(n: int):
+    """n torch streams whose work runs side by side.  A process owns a handful of hardware queues, two streams that
+    land on the same one serialise, and the API does not say which do: so candidates are tried pairwise with a
+    spin kernel per stream (two spins take the time of one only when the streams are concurrent).  Returns
+    (streams, found): found is False when fewer than n mutually concurrent streams turned up among the
+    candidates; the list is then filled up with streams that share a queue with another one."""
+    cur = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    spin = 2_000_000      # about a millisecond
+
+    def both(a, b) -> float:
+        torch.cuda.synchronize()
+        e0.record()
+        for st in (a, b):
+            st.wait_stream(cur)
+            with torch.cuda.stream(st):
+                torch.cuda._sleep(spin)
+        cur.wait_stream(a)
+        cur.wait_stream(b)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1)
+
+    candidates = [torch.cuda.Stream() for _ in range(12)]
+    both(candidates[0], candidates[0])
+    alone = min(both(c, c) for c in candidates[:2]) / 2
+    chosen = [candidates[0]]
+    for c in candidates[1:]:
+        if len(chosen) == n:
+            break
+        if all(both(c, k) < 1.5 * alone for k in chosen):
+            chosen.append(c)
+    concurrent = len(chosen) == n
+    chosen += [c for c in candidates if c not in chosen][:n - len(chosen)]
+    return chosen, concurrent

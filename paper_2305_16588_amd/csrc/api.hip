@@ -1109,12 +1109,13 @@ int lgp_sample_extract(lgp_ctx* c, const int32_t* seeds, int32_t n_seeds, const 
   launch_begin_listing(c->di, seeds, n_seeds, out->gather_ids, c->seg, c->seg_counters, n_groups * 3, s);
   LGP_HIP(c, hipEventRecord(c->ev_group[0], s));
   LGP_HIP(c, hipStreamWaitEvent(x, c->ev_group[0], 0));
+  // from here on a failed step stops the enqueueing but not the clean-up below: the bitmaps must be clear and
+  // `stream` must have joined the library's stream whatever the call returns
   st = gather_core(c, -1, out->gather_ids, out->gather_cap, nullptr, rows, c->seg_counters, x, nullptr, 0, c->seg,
                    std::max<int64_t>(n_seeds, 1));
-  if (st != LGP_OK) return st;
   const int32_t* frontier = seeds;
   int64_t cap = n_seeds;
-  for (int h = 0; h < n_hops; ++h) {
+  for (int h = 0; h < n_hops && st == LGP_OK; ++h) {
     launch_sample_hop(c->di, tv, frontier, out->n_frontier + h, cap, fanouts[h], h, rng_seed, out->nbr[h], out->cnt[h],
                       fbits32, h == 0 ? gbits32 : nullptr, nullptr, c->d_err, s);
     // next frontier (if anyone needs it as a list) and the vertices this hop reached first, appended to the listing
@@ -1128,18 +1129,18 @@ int lgp_sample_extract(lgp_ctx* c, const int32_t* seeds, int32_t n_seeds, const 
     LGP_HIP(c, hipStreamWaitEvent(x, c->ev_group[h + 1], 0));
     st = gather_core(c, -1, out->gather_ids, out->gather_cap, nullptr, rows, c->seg_counters + 3 * (h + 1), x, nullptr, 0,
                      c->seg + h + 1, std::max<int64_t>(need[h + 1], 1));
-    if (st != LGP_OK) return st;
     frontier = next;
     cap = next ? out->cap[h + 1] : 0;
   }
   // the "seen" bitmap of this batch is not compacted (the listing replaces the ascending list), so clear it whole
   launch_fill_i32(c->di, reinterpret_cast<int32_t*>(c->gbits), c->n_chunks * kChunkWords * 2, 0, s);
-  if (stats) launch_sum_stats(c->seg_counters, n_groups, stats, x);
-  if (groups) {
+  if (st == LGP_OK && stats) launch_sum_stats(c->seg_counters, n_groups, stats, x);
+  if (st == LGP_OK && groups) {
     LGP_HIP(c, hipMemcpyAsync(groups, c->seg, sizeof(int32_t) * size_t(n_hops + 2), hipMemcpyDeviceToDevice, x));
   }
   LGP_HIP(c, hipEventRecord(c->ev_extracted, x));
   LGP_HIP(c, hipStreamWaitEvent(s, c->ev_extracted, 0));
+  if (st != LGP_OK) return st;
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail_hip(c, e, "intra-batch pipeline launch");
   return LGP_OK;

@@ -49,7 +49,8 @@ def main() -> None:
 
     ctx.set_overlap(0 < plan.n_feat < spec.num_vertices)        # both gathers have work: run them side by side
     n_batches = tablet.numel() // spec.batch
-    s_sample, s_gather, s_blocks = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    # streams that share a hardware queue would run one after the other, so pick three that do not
+    (s_sample, s_gather, s_blocks), _ = lgp.concurrent_streams(3)
     bufs = [lgp.SampleBuffers(spec.num_vertices, spec.batch, spec.fanouts, last_frontier=True) for _ in range(2)]
     blks = [lgp.BlockBuffers(b) for b in bufs]
     rows = [torch.empty((bufs[0].gather_cap, spec.feat_dim), dtype=ctx.feat_torch_dtype, device="cuda") for _ in range(2)]

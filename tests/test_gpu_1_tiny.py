@@ -355,7 +355,8 @@ def test_overlap_profiling_and_three_stream_pipelining(W):
     W.ctx.build_cache(*datagen.budgets(spec, W.E))
     refs = [W.orc.sample_khop(W.batch(b)[0], spec.fanouts, 600 + b, blocks=True) for b in range(4)]
     rows_ref = [W.orc.gather(r.gather_ids) for r in refs]
-    sA, sB, sC = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    (sA, sB, sC), found = lgp.concurrent_streams(3)           # three streams, on hardware queues of their own if possible
+    assert isinstance(found, bool) and len({sA.cuda_stream, sB.cuda_stream, sC.cuda_stream}) == 3
     bufs = [lgp.SampleBuffers(W.V, spec.batch, spec.fanouts, last_frontier=True) for _ in range(2)]
     blks = [lgp.BlockBuffers(bufs[k]) for k in range(2)]
     W.ctx.build_blocks(W.batch(0)[1], spec.fanouts, W.ctx.sample_khop(W.batch(0)[1], spec.fanouts, 1, out=bufs[0]),
