@@ -24,7 +24,7 @@ import datagen
 
 pytestmark = pytest.mark.gpu
 FULL = os.environ.get("LGP_SMALL", "0") != "1"
-HOT_BATCHES = 8
+HOT_BATCHES = 32
 
 
 def _spec(name):
