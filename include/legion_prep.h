@@ -123,13 +123,13 @@ int lgp_host_free(void* ptr);
  * vertex, filled from indptr), the feature remap, two hotness vectors and the dedup
  * bitmaps -- about 20.3 bytes per vertex, outside the cache budgets.  It starts with
  * empty caches, so sampling and gathering already work, with every column id and
- * feature row read from CPU memory (the "topology in CPU memory" mode of Sec. 3.2).
+ * feature row read from CPU memory (Sec. 3.2's mode with the topology kept in CPU memory).
  * Synchronous. */
 int lgp_create(const lgp_graph* g, int device, lgp_ctx** out);
 int lgp_destroy(lgp_ctx* ctx);
 
-/* Batch generator (Sec. 5, operator 1: "shuffles the local training vertices to generate
- * seeds for mini batches").  out[j] = in[pi(j)] where pi orders the positions 0 .. n-1 by the
+/* Batch generator (Sec. 5, the first operator of the sampling server: a per-epoch shuffle of
+ * this GPU's training vertices, cut into mini-batches of seeds).  out[j] = in[pi(j)] where pi orders the positions 0 .. n-1 by the
  * 64-bit Philox4x32-10 draw keyed (seed, position, epoch, 0), ascending, ties by position:
  * a reproducible permutation per epoch.  in / out are [device], n ids each, and must not
  * overlap.  Needs no context; runs on `device`; allocates sort scratch; synchronous. */
@@ -258,8 +258,8 @@ int lgp_get_cache_part(lgp_ctx* ctx, int32_t which, int64_t first, int64_t count
 int lgp_sample_khop(lgp_ctx* ctx, const int32_t* seeds, int32_t n_seeds, const int32_t* fanouts, int32_t n_hops,
                     uint64_t rng_seed, const lgp_sample_out* out, void* stream);
 
-/* One mini-batch through the intra-batch pipeline of Sec. 5 ("for the same batch, graph sampling ... can be
- * overlapped with feature extraction"): lgp_sample_khop and lgp_gather_features in one call, with the
+/* One mini-batch through the intra-batch pipeline of Sec. 5 (one batch's sampling runs beside its own
+ * feature extraction): lgp_sample_khop and lgp_gather_features in one call, with the
  * extraction running on a stream of the library's own beside the sampling.  That is only possible if rows are
  * extracted in the order in which the sampler reaches their vertices, so out->gather_ids is not the ascending
  * list here but the listing
@@ -279,8 +279,8 @@ int lgp_sample_extract(lgp_ctx* ctx, const int32_t* seeds, int32_t n_seeds, cons
                        uint64_t rng_seed, const lgp_sample_out* out, void* rows, int32_t* groups, int32_t* stats,
                        void* stream);
 
-/* Graph constructor (Sec. 5, operator 4: "generating the subgraph based on the sampled
- * results").  Takes the buffers a finished lgp_sample_khop call filled (same seeds, fanouts
+/* Graph constructor (Sec. 5, the fourth operator: it turns the sampled neighbour lists into the
+ * per-hop subgraph).  Takes the buffers a finished lgp_sample_khop call filled (same seeds, fanouts
  * and `sampled`, with sampled->frontier[n_hops] given) and writes, per hop h, a bipartite
  * block in CSR form whose destinations are frontier h and whose sources are frontier h+1,
  * plus for every frontier the rows of its vertices in the extracted feature matrix.

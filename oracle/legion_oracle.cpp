@@ -18,14 +18,14 @@
 //   * cache size rule (Eq. 3 and Eq. 6): a cached topology row costs
 //     4 bytes per neighbour plus 8 bytes; a cached feature row costs
 //     D * element size.  The cached set is the longest prefix of the ranking
-//     whose total cost does not exceed the budget (paper: "until the size
-//     reaches m"; read as <=).
+//     whose total cost does not exceed the budget (the paper fills the cache
+//     up to size m; read as <=).
 //   * cache layout (Sec. 4.2.1): topology cache = CSR over the cached rows in
 //     rank order; feature cache = 2-D array, one row per cached vertex in rank
 //     order.
 //   * RNG (paper silent): Philox4x32-10 (Salmon et al., SC'11), one call per
 //     (seed, vertex, hop, slot).
-//   * subset selection (paper says only "uniform, fixed-size"): rows with
+//   * subset selection (the paper only asks for a uniform sample of fixed size): rows with
 //     degree <= fanout are returned whole; otherwise Floyd's subset algorithm.
 //   * frontier semantics (paper silent): the next frontier is the ascending
 //     sorted set of the current hop's sampled neighbours; the set of vertices
@@ -220,8 +220,8 @@ const int32_t* orc_batch_gather_ids(const void* h) { return static_cast<const Ba
 void orc_batch_free(void* h) { delete static_cast<Batch*>(h); }
 
 // --- batch generator (Sec. 5, operator 1) -------------------------------------
-// "Shuffles the local training vertices to generate seeds for mini batches."  The paper names
-// no shuffle; here position i of the tablet gets the 64-bit key draw64(seed, i, epoch, 0) and
+// The operator reorders this GPU's training vertices once per epoch and cuts the order into
+// mini-batches of seeds.  The paper names no particular shuffle; here position i of the tablet gets the 64-bit key draw64(seed, i, epoch, 0) and
 // the tablet is reordered by ascending key (ties by position), so every epoch has its own
 // reproducible order.
 void orc_shuffle_tablet(const int32_t* in, int32_t* out, int64_t n, uint64_t seed, uint32_t epoch) {
@@ -232,8 +232,8 @@ void orc_shuffle_tablet(const int32_t* in, int32_t* out, int64_t n, uint64_t see
 }
 
 // --- graph constructor (Sec. 5, operator 4) ----------------------------------
-// The paper only says the constructor "generates the subgraph based on the sampled
-// results".  Reading used here: hop h becomes a bipartite block in CSR form whose
+// The paper only says that the constructor builds the subgraph from the sampler's
+// output.  Reading used here: hop h becomes a bipartite block in CSR form whose
 // destinations are frontier h (in order) and whose sources are frontier h+1;
 // blk_indptr[i] = number of sampled edges of destinations before i, blk_src[e] = position of
 // the e-th sampled neighbour inside frontier h+1; feat_row[i] = position of frontier h's i-th
